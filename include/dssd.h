@@ -1,0 +1,149 @@
+/* dssd.h - C ABI of the batched speculative-decoding verification step of DSSD
+ * (Distributed Split Speculative Decoding, arXiv 2507.12000) for AMD MI355X (gfx950).
+ *
+ * The paper cuts one verification round in two (Sec. 3, Algorithm 2):
+ *   edge   : accept/reject every draft token against the target model's distributions and,
+ *            if all are accepted, draw the bonus token           -> dssd_verify_batch,
+ *                                                                   dssd_bonus_sample
+ *   device : if a draft was rejected at position j, redraw it from
+ *            norm(max(0, P_j - Q_j))                             -> dssd_residual_sample
+ * Running the three calls back to back on one GPU is the unsplit scheme (Sec. 2.1, Algorithm 1).
+ *
+ * Conventions
+ *   - Every pointer inside dssd_batch / dssd_out is a DEVICE pointer owned by the caller; the
+ *     library never frees or reallocates it.  The structs themselves live in HOST memory and
+ *     are read during the call only.
+ *   - All three hot calls are asynchronous on `hip_stream` (a hipStream_t, NULL = default
+ *     stream); they never synchronise, never allocate and never touch host copies of the data.
+ *   - dssd_residual_sample and dssd_bonus_sample must follow dssd_verify_batch for the same
+ *     batch on the same context and stream: they read accepted_len / rejected and the softmax
+ *     statistics that verify left in the context's workspace.
+ *   - One context serves one stream at a time (its workspace is shared by consecutive calls).
+ *   - Positions are 0-based: accepted_len = j - 1 in the paper's numbering.
+ *   - Host-checkable errors return a negative status before anything is launched.  Errors that
+ *     only the device can see (token id outside [0,V), inconsistent offsets, a logits row whose
+ *     softmax is not finite) set status[b] and give that session accepted_len = 0,
+ *     rejected = 1, out_token = -1; the samplers skip it.
+ */
+#ifndef DSSD_H
+#define DSSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dssd_ctx dssd_ctx; /* opaque: device workspace + profiling events */
+
+typedef enum { DSSD_F32 = 0, DSSD_BF16 = 1 } dssd_dtype;
+
+typedef enum {
+  DSSD_OK = 0,
+  DSSD_EINVAL = -1,       /* NULL required pointer, negative size, unknown dtype        */
+  DSSD_EALIGN = -2,       /* a pointer is not aligned to its element size                */
+  DSSD_ENOMEM = -3,       /* batch larger than the context's workspace / allocation failed */
+  DSSD_EHIP = -4,         /* a HIP runtime call failed                                   */
+  DSSD_EUNSUPPORTED = -5
+} dssd_status;
+
+/* Per-session bits written to dssd_out.status (device side). */
+enum {
+  DSSD_SESSION_BAD_TOKEN = 1,    /* a draft token outside [0, V)                          */
+  DSSD_SESSION_ZERO_RESIDUAL = 2,/* residual mass rounded to 0: token drawn from P_j       */
+  DSSD_SESSION_BAD_OFFSETS = 4,  /* draft_offsets not monotone or beyond total_drafts      */
+  DSSD_SESSION_BAD_ROW = 8       /* a softmax sum or maximum that is not finite/positive,
+                                    or an inverse temperature that is not finite/positive  */
+};
+
+/* Input of one verification step for B sessions (Sec. 2.1 "Verification Process";
+ * Algorithm 2, inputs of the edge: tokens x_1..x_gamma, values q_j(x_j), and P_1..P_{gamma+1}).
+ *
+ * Session b owns draft rows [off_b, off_b + gamma_b) and logits rows
+ * [off_b + b, off_b + b + gamma_b]  (gamma_b + 1 of them), where off_b = draft_offsets[b]
+ * and gamma_b = draft_offsets[b+1] - draft_offsets[b], or off_b = b*gamma, gamma_b = gamma
+ * when draft_offsets is NULL.  R_Q = total_drafts rows of drafts, R_L = R_Q + B rows of logits.
+ */
+typedef struct {
+  int32_t B;                    /* sessions; 0 is a no-op                                          */
+  int32_t V;                    /* vocabulary size |V|, >= 1                                       */
+  int32_t gamma;                /* drafts per session when draft_offsets == NULL, >= 0             */
+  int32_t logits_dtype;         /* dssd_dtype of `logits`                                          */
+  int64_t total_drafts;         /* R_Q = sum of gamma_b (must equal B*gamma when offsets == NULL)  */
+  const int32_t *draft_offsets; /* [B+1] prefix sums of gamma_b, or NULL for uniform gamma         */
+  const void *logits;           /* [R_L, V] row-major contiguous target logits, fp32 or bf16       */
+  const float *draft_probs;     /* [R_Q, V] row-major fp32 draft distributions Q_i, each row
+                                   already a probability vector; used as given                     */
+  const int32_t *draft_tokens;  /* [R_Q] draft token ids x_i in [0, V)                             */
+  const float *inv_temperature; /* [B] 1/T_b > 0 multiplying the target logits before the softmax,
+                                   or NULL for T = 1 (the paper's setting)                         */
+  uint64_t seed;                /* Philox4x32-10 key (lo, hi)                                      */
+  uint64_t step;                /* verify-step number; Philox counter = (session_base + b,
+                                   position, step lo, step hi).  Word 0 of the block drives the
+                                   accept test at that position, word 1 the residual draw at that
+                                   position, word 2 the bonus draw (position gamma_b)              */
+  uint32_t session_base;        /* global id of session 0 (keeps results independent of sharding)  */
+  uint32_t reserved;
+} dssd_batch;
+
+/* Output of one step: the paper's (x_j, j) record per session plus what the samplers and the
+ * parity checks need.  Required: accepted_len, rejected, out_token.  Optional (may be NULL):
+ * row_stats, p_tok, q_tok, status.
+ */
+typedef struct {
+  int32_t *accepted_len; /* [B] n_b in [0, gamma_b]: number of accepted drafts (j - 1)             */
+  int32_t *rejected;     /* [B] 1 iff n_b < gamma_b (Flag = 0; the indicator `a` of Sec. 3.1)      */
+  int32_t *out_token;    /* [B] redrawn token (rejected) or bonus token (all accepted)             */
+  float *row_stats;      /* [R_L, 2]: (m, Z) with m = max_v z_v/T, Z = sum_v exp(z_v/T - m), so
+                            P(v) = exp(z_v/T - m)/Z                                                */
+  float *p_tok;          /* [R_Q] p_i(x_i) for every draft position                                */
+  float *q_tok;          /* [R_Q] q_i(x_i): the scalars DSSD uploads instead of the Q rows         */
+  int32_t *status;       /* [B] DSSD_SESSION_* bits, 0 when fine                                   */
+} dssd_out;
+
+/* Bytes of device workspace a context needs for up to max_rows logits rows of max_V entries. */
+size_t dssd_workspace_bytes(int64_t max_rows, int32_t max_V, int32_t logits_dtype);
+
+/* Create a context on HIP device `device`, with workspace for batches of up to max_rows logits
+ * rows (R_L) and vocabularies up to max_V, for either logits dtype.  The only call that
+ * allocates device memory.  Fails with DSSD_EHIP when no usable GPU is present. */
+dssd_status dssd_create(dssd_ctx **ctx, int device, int64_t max_rows, int32_t max_V);
+void dssd_destroy(dssd_ctx *ctx);
+
+/* Edge side, Algorithm 2 "Verification Process": softmax statistics of all R_L logits rows
+ * (each row is read from memory once), then per draft position
+ *   accept_i  <=>  r_i * q_i(x_i) < p_i(x_i)     (r_i < min(1, p/q), r_i in [0,1))
+ * and n_b = index of the first rejected draft, or gamma_b.  Writes accepted_len, rejected and
+ * the optional outputs.  out_token is written only for sessions with a device-side error. */
+dssd_status dssd_verify_batch(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
+
+/* Device side, Algorithm 2 "Resample" (Algorithm 1 "Reject and Resample"): for every session
+ * with rejected = 1, out_token = x ~ norm(max(0, P_n - Q_n)) at n = accepted_len, by inverse
+ * CDF in vocabulary order with r = word 1 of the position-n block: the smallest k whose
+ * inclusive prefix sum exceeds r * R, R the residual mass.  Other sessions are untouched. */
+dssd_status dssd_residual_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
+
+/* Edge side, Algorithm 2: for every session with rejected = 0, out_token = x ~ P_{gamma_b+1}
+ * (the last logits row of the session) by the same inverse-CDF rule with r = word 2 of the
+ * position-gamma_b block.  Other sessions are untouched. */
+dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
+
+const char *dssd_status_str(dssd_status s);
+
+/* Kernel timing (measurement aid, not on the hot path).  While enabled, every kernel launch is
+ * bracketed by HIP events on the launch stream.  Kernel ids: 0 row softmax statistics,
+ * 1 accept / first-reject, 2 residual chunk masses, 3 residual pick, 4 bonus pick. */
+enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
+       DSSD_K_BONUS_PICK = 4, DSSD_K_COUNT = 5 };
+dssd_status dssd_profile_enable(dssd_ctx *ctx, int enable);
+/* Synchronises the recorded events, returns the summed duration (ms) and number of launches
+ * of one kernel since the last reset. */
+dssd_status dssd_profile_read(dssd_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
+dssd_status dssd_profile_reset(dssd_ctx *ctx);
+const char *dssd_kernel_name(int kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSSD_H */

@@ -1,0 +1,249 @@
+// C ABI of the DSSD verification library (see include/dssd.h): argument checks, workspace,
+// kernel launches, optional per-kernel event timing.  No step of the method runs on the host.
+#include "../../include/dssd.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "dssd_kernels.hpp"
+
+using namespace dssd;
+
+struct dssd_ctx {
+  int device = 0;
+  int64_t max_rows = 0;
+  int32_t max_V = 0;
+  int32_t max_C = 0;
+  void* workspace = nullptr;
+  float2* chunk_stats = nullptr;
+  float2* row_tab = nullptr;
+  float* resid_mass = nullptr;
+  int32_t* skip = nullptr;
+  bool profiling = false;
+  std::vector<hipEvent_t> ev_begin[DSSD_K_COUNT], ev_end[DSSD_K_COUNT];
+  size_t ev_used[DSSD_K_COUNT] = {0, 0, 0, 0, 0};
+};
+
+static inline int32_t chunks_per_row(int32_t V, int32_t dtype) {
+  const int32_t ce = dtype == DSSD_BF16 ? chunk_elems<true>() : chunk_elems<false>();
+  return (V + ce - 1) / ce;
+}
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+extern "C" size_t dssd_workspace_bytes(int64_t max_rows, int32_t max_V, int32_t logits_dtype) {
+  if (max_rows < 1 || max_V < 1) return 0;
+  const size_t C = (size_t)chunks_per_row(max_V, logits_dtype);
+  const size_t rows = (size_t)max_rows;
+  return align256(rows * C * sizeof(float2)) + align256(rows * sizeof(float2)) +
+         align256(rows * C * sizeof(float)) + align256(rows * sizeof(int32_t));
+}
+
+extern "C" const char* dssd_status_str(dssd_status s) {
+  switch (s) {
+    case DSSD_OK: return "ok";
+    case DSSD_EINVAL: return "invalid argument";
+    case DSSD_EALIGN: return "misaligned pointer";
+    case DSSD_ENOMEM: return "batch exceeds workspace or allocation failed";
+    case DSSD_EHIP: return "HIP runtime error";
+    case DSSD_EUNSUPPORTED: return "unsupported";
+  }
+  return "unknown status";
+}
+
+extern "C" const char* dssd_kernel_name(int k) {
+  static const char* names[DSSD_K_COUNT] = {"row_chunk_stats", "accept_scan", "resid_mass",
+                                            "resid_pick", "bonus_pick"};
+  return (k >= 0 && k < DSSD_K_COUNT) ? names[k] : "?";
+}
+
+extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows, int32_t max_V) {
+  if (!out || max_rows < 1 || max_V < 1 || device < 0) return DSSD_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device >= count) return DSSD_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return DSSD_EHIP;
+  dssd_ctx* c = new (std::nothrow) dssd_ctx;
+  if (!c) return DSSD_ENOMEM;
+  c->device = device;
+  c->max_rows = max_rows;
+  c->max_V = max_V;
+  c->max_C = chunks_per_row(max_V, DSSD_F32);  // fp32 chunks hold fewer elements: the larger count
+  const size_t bytes = dssd_workspace_bytes(max_rows, max_V, DSSD_F32);
+  if (hipMalloc(&c->workspace, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    delete c;
+    return DSSD_ENOMEM;
+  }
+  char* p = static_cast<char*>(c->workspace);
+  const size_t rows = (size_t)max_rows, C = (size_t)c->max_C;
+  c->chunk_stats = reinterpret_cast<float2*>(p); p += align256(rows * C * sizeof(float2));
+  c->row_tab = reinterpret_cast<float2*>(p);     p += align256(rows * sizeof(float2));
+  c->resid_mass = reinterpret_cast<float*>(p);   p += align256(rows * C * sizeof(float));
+  c->skip = reinterpret_cast<int32_t*>(p);
+  *out = c;
+  return DSSD_OK;
+}
+
+extern "C" void dssd_destroy(dssd_ctx* c) {
+  if (!c) return;
+  for (int k = 0; k < DSSD_K_COUNT; ++k) {
+    for (hipEvent_t e : c->ev_begin[k]) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->ev_end[k]) (void)hipEventDestroy(e);
+  }
+  if (c->workspace) (void)hipFree(c->workspace);
+  delete c;
+}
+
+// Host-side checks shared by the three hot calls.  Fills the kernel argument block.
+static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const dssd_out* o, BatchView* v) {
+  if (!c || !b || !o) return DSSD_EINVAL;
+  if (b->B < 0 || b->V < 1 || b->gamma < 0 || b->total_drafts < 0) return DSSD_EINVAL;
+  if (b->logits_dtype != DSSD_F32 && b->logits_dtype != DSSD_BF16) return DSSD_EINVAL;
+  if (!b->draft_offsets && b->total_drafts != (int64_t)b->B * b->gamma) return DSSD_EINVAL;
+  if (b->B > 0) {
+    if (!b->logits || !o->accepted_len || !o->rejected || !o->out_token) return DSSD_EINVAL;
+    if (b->total_drafts > 0 && (!b->draft_probs || !b->draft_tokens)) return DSSD_EINVAL;
+  }
+  const uintptr_t esz = b->logits_dtype == DSSD_BF16 ? 2 : 4;
+  auto mis = [](const void* p, uintptr_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) != 0; };
+  if (mis(b->logits, esz) || mis(b->draft_probs, 4) || mis(b->draft_tokens, 4) || mis(b->draft_offsets, 4) ||
+      mis(b->inv_temperature, 4) || mis(o->accepted_len, 4) || mis(o->rejected, 4) || mis(o->out_token, 4) ||
+      mis(o->row_stats, 4) || mis(o->p_tok, 4) || mis(o->q_tok, 4) || mis(o->status, 4))
+    return DSSD_EALIGN;
+  const int64_t R_L = b->total_drafts + b->B;
+  const int32_t C = chunks_per_row(b->V, b->logits_dtype);
+  if (R_L > c->max_rows || b->V > c->max_V || C > c->max_C) return DSSD_ENOMEM;
+  v->B = b->B; v->V = b->V; v->gamma = b->gamma; v->C = C;
+  v->R_L = R_L; v->R_Q = b->total_drafts;
+  v->offsets = b->draft_offsets; v->logits = b->logits; v->draft_probs = b->draft_probs;
+  v->tokens = b->draft_tokens; v->inv_temp = b->inv_temperature;
+  v->seed_lo = (uint32_t)b->seed; v->seed_hi = (uint32_t)(b->seed >> 32);
+  v->step_lo = (uint32_t)b->step; v->step_hi = (uint32_t)(b->step >> 32);
+  v->session_base = b->session_base;
+  v->accepted_len = o->accepted_len; v->rejected = o->rejected; v->out_token = o->out_token;
+  v->row_stats = o->row_stats; v->p_tok = o->p_tok; v->q_tok = o->q_tok; v->status = o->status;
+  v->chunk_stats = c->chunk_stats; v->row_tab = c->row_tab; v->resid_mass = c->resid_mass; v->skip = c->skip;
+  return DSSD_OK;
+}
+
+// 128-bit loads need 16-byte aligned rows: aligned bases and V a multiple of the vector width.
+static bool vector_ok(const dssd_batch* b) {
+  const int per_vec = b->logits_dtype == DSSD_BF16 ? 8 : 4;
+  auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  return (b->V % per_vec) == 0 && al16(b->logits) && al16(b->draft_probs);
+}
+
+namespace {
+struct Timed {
+  dssd_ctx* c; int k; hipStream_t s; hipEvent_t end = nullptr; bool failed = false;
+  Timed(dssd_ctx* c_, int k_, hipStream_t s_) : c(c_), k(k_), s(s_) {
+    if (!c->profiling) return;
+    if (c->ev_used[k] == c->ev_begin[k].size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { failed = true; return; }
+      c->ev_begin[k].push_back(a);
+      c->ev_end[k].push_back(b);
+    }
+    const size_t i = c->ev_used[k]++;
+    end = c->ev_end[k][i];
+    if (hipEventRecord(c->ev_begin[k][i], s) != hipSuccess) failed = true;
+  }
+  ~Timed() { if (end) (void)hipEventRecord(end, s); }
+};
+}  // namespace
+
+#define DSSD_LAUNCH(kernel, grid, stream, ...)                                   \
+  do {                                                                           \
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(256), 0, stream, __VA_ARGS__); \
+  } while (0)
+
+static dssd_status launch_status() { return hipGetLastError() == hipSuccess ? DSSD_OK : DSSD_EHIP; }
+
+extern "C" dssd_status dssd_verify_batch(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
+  BatchView v;
+  const dssd_status st = check_and_view(c, b, o, &v);
+  if (st != DSSD_OK || b->B == 0) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  const int64_t tasks = v.R_L * v.C;
+  if ((tasks + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+  const unsigned grid = (unsigned)((tasks + 3) / 4);
+  {
+    Timed t(c, DSSD_K_ROW_STATS, s);
+    if (bf16) { if (al) DSSD_LAUNCH((row_chunk_stats<true, true>), grid, s, v); else DSSD_LAUNCH((row_chunk_stats<true, false>), grid, s, v); }
+    else      { if (al) DSSD_LAUNCH((row_chunk_stats<false, true>), grid, s, v); else DSSD_LAUNCH((row_chunk_stats<false, false>), grid, s, v); }
+  }
+  {
+    Timed t(c, DSSD_K_ACCEPT, s);
+    const unsigned g2 = (unsigned)((b->B + 3) / 4);
+    if (bf16) DSSD_LAUNCH((accept_scan<true>), g2, s, v); else DSSD_LAUNCH((accept_scan<false>), g2, s, v);
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
+  BatchView v;
+  const dssd_status st = check_and_view(c, b, o, &v);
+  if (st != DSSD_OK || b->B == 0) return st;
+  if (b->total_drafts == 0) return DSSD_OK;   // nothing can have been rejected
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  const int32_t groups = (v.C + 3) / 4;
+  if ((int64_t)groups * b->B > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+  const unsigned grid = (unsigned)(groups * b->B);
+  {
+    Timed t(c, DSSD_K_RESID_MASS, s);
+    if (bf16) { if (al) DSSD_LAUNCH((resid_mass<true, true>), grid, s, v, groups); else DSSD_LAUNCH((resid_mass<true, false>), grid, s, v, groups); }
+    else      { if (al) DSSD_LAUNCH((resid_mass<false, true>), grid, s, v, groups); else DSSD_LAUNCH((resid_mass<false, false>), grid, s, v, groups); }
+  }
+  {
+    Timed t(c, DSSD_K_RESID_PICK, s);
+    const unsigned g2 = (unsigned)((b->B + 3) / 4);
+    if (bf16) { if (al) DSSD_LAUNCH((pick_token<true, true, true>), g2, s, v); else DSSD_LAUNCH((pick_token<true, false, true>), g2, s, v); }
+    else      { if (al) DSSD_LAUNCH((pick_token<false, true, true>), g2, s, v); else DSSD_LAUNCH((pick_token<false, false, true>), g2, s, v); }
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_bonus_sample(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
+  BatchView v;
+  const dssd_status st = check_and_view(c, b, o, &v);
+  if (st != DSSD_OK || b->B == 0) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  {
+    Timed t(c, DSSD_K_BONUS_PICK, s);
+    const unsigned g2 = (unsigned)((b->B + 3) / 4);
+    if (bf16) { if (al) DSSD_LAUNCH((pick_token<true, true, false>), g2, s, v); else DSSD_LAUNCH((pick_token<true, false, false>), g2, s, v); }
+    else      { if (al) DSSD_LAUNCH((pick_token<false, true, false>), g2, s, v); else DSSD_LAUNCH((pick_token<false, false, false>), g2, s, v); }
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_profile_enable(dssd_ctx* c, int enable) {
+  if (!c) return DSSD_EINVAL;
+  c->profiling = enable != 0;
+  return DSSD_OK;
+}
+
+extern "C" dssd_status dssd_profile_reset(dssd_ctx* c) {
+  if (!c) return DSSD_EINVAL;
+  for (int k = 0; k < DSSD_K_COUNT; ++k) c->ev_used[k] = 0;
+  return DSSD_OK;
+}
+
+extern "C" dssd_status dssd_profile_read(dssd_ctx* c, int k, double* total_ms, int64_t* launches) {
+  if (!c || k < 0 || k >= DSSD_K_COUNT || !total_ms || !launches) return DSSD_EINVAL;
+  double sum = 0.0;
+  for (size_t i = 0; i < c->ev_used[k]; ++i) {
+    if (hipEventSynchronize(c->ev_end[k][i]) != hipSuccess) return DSSD_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev_begin[k][i], c->ev_end[k][i]) != hipSuccess) return DSSD_EHIP;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)c->ev_used[k];
+  return DSSD_OK;
+}

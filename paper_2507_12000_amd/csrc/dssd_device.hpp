@@ -1,0 +1,146 @@
+// Device-side building blocks of the DSSD verification kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dssd {
+
+constexpr int kWave = 64;
+constexpr int kUnroll = 8;                    // 16-byte vectors per lane per chunk
+constexpr int kChunkVecs = kWave * kUnroll;   // 512 vectors = 8 KiB of logits per chunk
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <bool BF16> struct Elems { static constexpr int per_vec = BF16 ? 8 : 4; };
+template <bool BF16> constexpr int chunk_elems() { return kChunkVecs * Elems<BF16>::per_vec; }
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float neg_inf() { return as_float(0xFF800000u); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// largest float below a positive finite x
+__device__ __forceinline__ float next_below(float x) { return as_float(as_u32(x) - 1u); }
+
+// ------------------------------------------------------------------ Philox4x32-10
+// Counter-based generator of Salmon, Moraes, Dror and Shaw (SC'11): ten rounds, each
+// replacing (c0,c1,c2,c3) by (hi(B*c2)^c1^k0, lo(B*c2), hi(A*c0)^c3^k1, lo(A*c0)) and then
+// advancing the key by two Weyl constants.
+struct Philox {
+  uint32_t w[4];
+  __device__ __forceinline__ Philox(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                    uint32_t k1) {
+    constexpr uint32_t A = 0xD2511F53u, Bm = 0xCD9E8D57u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+      const uint32_t hiA = __umulhi(A, c0), loA = A * c0;
+      const uint32_t hiB = __umulhi(Bm, c2), loB = Bm * c2;
+      const uint32_t n0 = hiB ^ c1 ^ k0, n2 = hiA ^ c3 ^ k1;
+      c0 = n0; c1 = loB; c2 = n2; c3 = loA;
+      k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
+  }
+};
+// top 24 bits -> [0,1), exact in fp32
+__device__ __forceinline__ float u01(uint32_t word) { return (float)(word >> 8) * 5.9604644775390625e-8f; }
+
+// ------------------------------------------------------------------ wave64 reductions (DPP)
+template <int CTRL> __device__ __forceinline__ float dpp(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float lane_value(float x, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
+// Every lane receives the result.  Fixed pairing order: xor 1, xor 2, mirror within 8, mirror
+// within 16, then the four rows of 16 lanes.
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp<0xB1>(x));    // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp<0x4E>(x));    // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp<0x141>(x));   // row_half_mirror
+  x = fmaxf(x, dpp<0x140>(x));   // row_mirror
+  return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  x += dpp<0xB1>(x);
+  x += dpp<0x4E>(x);
+  x += dpp<0x141>(x);
+  x += dpp<0x140>(x);
+  return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
+}
+// Inclusive prefix sum over the 64 lanes, in lane order.
+__device__ __forceinline__ float wave_scan(float x, int lane) {
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const float up = __shfl_up(x, d, kWave);
+    if (lane >= d) x += up;
+  }
+  return x;
+}
+
+// ------------------------------------------------------------------ row access
+// Loads the `vec`-th group of per_vec consecutive logits of a row as floats.  Entries at or
+// beyond V read as -inf.  ALIGNED: the row starts on a 16-byte boundary and V is a multiple of
+// per_vec, so the group is one 128-bit load.
+template <bool BF16, bool ALIGNED>
+__device__ __forceinline__ void load_logits(const void* row, int64_t vec, int32_t V, float* z) {
+  constexpr int E = Elems<BF16>::per_vec;
+  const int64_t e0 = vec * E;
+  if constexpr (ALIGNED) {
+    if (e0 < V) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(static_cast<const char*>(row) + vec * 16);
+      if constexpr (BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          z[2 * i] = as_float(v[i] << 16);
+          z[2 * i + 1] = as_float(v[i] & 0xFFFF0000u);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) z[i] = as_float(v[i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < E; ++i) z[i] = neg_inf();
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const int64_t e = e0 + i;
+      float x = neg_inf();
+      if (e < V) {
+        if constexpr (BF16) x = as_float((uint32_t) static_cast<const uint16_t*>(row)[e] << 16);
+        else x = static_cast<const float*>(row)[e];
+      }
+      z[i] = x;
+    }
+  }
+}
+__device__ __forceinline__ float load_logit(const void* row, int64_t e, bool bf16) {
+  return bf16 ? as_float((uint32_t) static_cast<const uint16_t*>(row)[e] << 16)
+              : static_cast<const float*>(row)[e];
+}
+// Loads draft probabilities [e0, e0+N) of a row; entries at or beyond V read as 0.
+template <int N, bool ALIGNED>
+__device__ __forceinline__ void load_probs(const float* row, int64_t e0, int32_t V, float* q) {
+  if constexpr (ALIGNED) {
+    if (e0 < V) {
+#pragma unroll
+      for (int i = 0; i < N / 4; ++i) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(row + e0 + 4 * i);
+        q[4 * i] = v[0]; q[4 * i + 1] = v[1]; q[4 * i + 2] = v[2]; q[4 * i + 3] = v[3];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) q[i] = 0.f;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) q[i] = (e0 + i < V) ? row[e0 + i] : 0.f;
+  }
+}
+
+}  // namespace dssd

@@ -1,0 +1,387 @@
+// Kernels of the DSSD verification step (arXiv 2507.12000, Sec. 2.1 / Sec. 3, Algorithms 1-2)
+// for gfx950.  Everything here is a streaming reduction or scan over the vocabulary, so the
+// kernels are organised around one unit of work: a *chunk* of 512 16-byte vectors (8 KiB) of
+// one logits row, owned by one 64-lane wave, which keeps the chunk in registers.
+//
+//   row_chunk_stats : per chunk, m2_c = max(z) * c1 and s_c = sum 2^(z*c1 - m2_c), with
+//                     c1 = log2(e)/T.  One exp per element, no cross-wave traffic.
+//   accept_scan     : per session, merges the chunk pairs into row (M2, Z), gathers p_i(x_i) and
+//                     q_i(x_i), draws r_i, and finds the first rejected draft with a ballot.
+//   resid_mass      : per chunk of the rejected row, the mass of max(0, P - Q).
+//   resid_pick / bonus_pick : scan the chunk masses, then re-read the one chunk that holds
+//                     r * total and locate the token by a wave prefix sum.
+#pragma once
+#include "dssd_device.hpp"
+
+namespace dssd {
+
+struct BatchView {
+  int32_t B, V, gamma, C;            // C = chunks per row
+  int64_t R_L, R_Q;
+  const int32_t* offsets;            // may be null
+  const void* logits;
+  const float* draft_probs;
+  const int32_t* tokens;
+  const float* inv_temp;             // may be null
+  uint32_t seed_lo, seed_hi, step_lo, step_hi, session_base;
+  // outputs
+  int32_t* accepted_len;
+  int32_t* rejected;
+  int32_t* out_token;
+  float* row_stats;                  // may be null
+  float* p_tok;                      // may be null
+  float* q_tok;                      // may be null
+  int32_t* status;                   // may be null
+  // workspace
+  float2* chunk_stats;               // [R_L, C]  (m2_c, s_c)
+  float2* row_tab;                   // [R_L]     (M2, Z) in the log2 domain
+  float* resid_mass;                 // [B, C]
+  int32_t* skip;                     // [B] 1 = session had a device-side error
+};
+
+__device__ __forceinline__ int64_t session_first_draft(const BatchView& a, int32_t b) {
+  return a.offsets ? (int64_t)a.offsets[b] : (int64_t)b * a.gamma;
+}
+// Session that owns logits row `row`: the largest b with first_draft(b) + b <= row.
+__device__ __forceinline__ int32_t session_of_row(const BatchView& a, int64_t row) {
+  if (!a.offsets) return (int32_t)(row / (a.gamma + 1));
+  int32_t lo = 0, hi = a.B - 1;
+  while (lo < hi) {
+    const int32_t mid = (lo + hi + 1) >> 1;
+    if ((int64_t)a.offsets[mid] + mid <= row) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+template <bool BF16> __device__ __forceinline__ const char* logits_row(const BatchView& a, int64_t row) {
+  return static_cast<const char*>(a.logits) + row * (int64_t)a.V * (BF16 ? 2 : 4);
+}
+
+// ---------------------------------------------------------------------------------------
+// Softmax statistics, one wave per chunk.  Step "LLM gets the gamma+1 distributions" of the
+// verification process: P(v) = 2^(z_v*c1 - M2)/Z.  This kernel reads every logit exactly once.
+// ---------------------------------------------------------------------------------------
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
+  constexpr int E = Elems<BF16>::per_vec;
+  const int lane = threadIdx.x & 63;
+  const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (task >= a.R_L * a.C) return;
+  const int64_t row = task / a.C;
+  const int32_t c = (int32_t)(task - row * a.C);
+  float c1 = kLog2e;
+  if (a.inv_temp) c1 *= a.inv_temp[session_of_row(a, row)];
+  const char* src = logits_row<BF16>(a, row);
+  const int64_t v0 = (int64_t)c * kChunkVecs + lane;
+
+  float z[kUnroll][E];
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) load_logits<BF16, ALIGNED>(src, v0 + k * kWave, a.V, z[k]);
+
+  float mx = neg_inf();
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k)
+#pragma unroll
+    for (int e = 0; e < E; ++e) mx = fmaxf(mx, z[k][e]);
+  mx = wave_max(mx);
+
+  float m2 = neg_inf(), s = 0.f;
+  if (mx > neg_inf()) {
+    m2 = mx * c1;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k)
+#pragma unroll
+      for (int e = 0; e < E; ++e) acc[e & 3] += fast_exp2(fmaf(z[k][e], c1, -m2));
+    s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+  }
+  if (lane == 0) a.chunk_stats[task] = make_float2(m2, s);
+}
+
+// ---------------------------------------------------------------------------------------
+// Accept / reject and first-reject scan, one wave per session, lane i = draft position i.
+// Algorithm 2, "Verification Process" loop: accept x_i iff r_i < min(1, p_i(x_i)/q_i(x_i)),
+// evaluated as r_i*q < p; stop at the first failure.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float2 merge_row(const BatchView& a, int64_t row) {
+  const float2* cs = a.chunk_stats + row * a.C;
+  float M2 = neg_inf();
+  for (int32_t c = 0; c < a.C; ++c) M2 = fmaxf(M2, cs[c].x);
+  float Z = 0.f;
+  if (M2 > neg_inf())
+    for (int32_t c = 0; c < a.C; ++c) Z += cs[c].y * fast_exp2(cs[c].x - M2);
+  return make_float2(M2, Z);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
+  const int lane = threadIdx.x & 63;
+  const int32_t b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (b >= a.B) return;
+  const int64_t off0 = session_first_draft(a, b);
+  const int64_t off1 = a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma;
+  int32_t bad = 0;
+  if (off0 < 0 || off1 < off0 || off1 > a.R_Q) bad = 4;
+  float tau = 1.f;
+  if (a.inv_temp) {
+    tau = a.inv_temp[b];
+    if (!(tau > 0.f) || !(tau < 3.0e38f)) bad |= 8;
+  }
+  const int32_t g = bad & 4 ? 0 : (int32_t)(off1 - off0);
+  const int64_t lrow0 = off0 + b;
+  const float c1 = tau * kLog2e;
+  int32_t first_reject = g;
+  if (!(bad & 4)) {
+    for (int32_t base = 0; base <= g; base += kWave) {
+      const int32_t i = base + lane;
+      bool reject = false;
+      int32_t lane_bad = 0;
+      if (i <= g) {
+        const int64_t lrow = lrow0 + i;
+        const float2 st = merge_row(a, lrow);
+        a.row_tab[lrow] = st;
+        if (a.row_stats) {
+          a.row_stats[2 * lrow] = st.x * (kLn2);
+          a.row_stats[2 * lrow + 1] = st.y;
+        }
+        if (!(st.y > 0.f) || !(st.y < 3.0e38f) || !(fabsf(st.x) < 3.0e38f)) lane_bad |= 8;
+        if (i < g) {
+          const int64_t qrow = off0 + i;
+          const int32_t x = a.tokens[qrow];
+          float p = 0.f, q = 0.f;
+          if (x < 0 || x >= a.V) {
+            lane_bad |= 1;
+          } else {
+            const float zx = load_logit(logits_row<BF16>(a, lrow), x, BF16);
+            p = fast_exp2(fmaf(zx, c1, -st.x)) / st.y;
+            q = a.draft_probs[qrow * (int64_t)a.V + x];
+            const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)i, a.step_lo, a.step_hi, a.seed_lo,
+                             a.seed_hi);
+            const float r = u01(rnd.w[0]);
+            reject = !(__fmul_rn(r, q) < p);
+          }
+          if (a.p_tok) a.p_tok[qrow] = p;
+          if (a.q_tok) a.q_tok[qrow] = q;
+        }
+      }
+      const uint64_t rej_mask = __ballot(reject);
+      if (rej_mask && first_reject == g) first_reject = base + (__ffsll((long long)rej_mask) - 1);
+      const uint64_t b1 = __ballot(lane_bad & 1), b8 = __ballot(lane_bad & 8);
+      bad |= (b1 ? 1 : 0) | (b8 ? 8 : 0);
+    }
+  }
+  if (lane == 0) {
+    if (bad) {
+      a.accepted_len[b] = 0;
+      a.rejected[b] = 1;
+      a.out_token[b] = -1;
+    } else {
+      a.accepted_len[b] = first_reject;
+      a.rejected[b] = first_reject < g ? 1 : 0;
+    }
+    a.skip[b] = bad ? 1 : 0;
+    if (a.status) a.status[b] = bad;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Weights of one 16-byte group of a row, shared by the mass and pick kernels so that both
+// see bit-identical values: w = max(0, 2^(z*c1 - M2)*invZ - q) (residual, Algorithm 2
+// "Resample") or w = 2^(z*c1 - M2) (bonus draw from P).
+// ---------------------------------------------------------------------------------------
+template <bool BF16, bool ALIGNED, bool RESID>
+__device__ __forceinline__ float group_weights(const char* lrow, const float* qrow, int64_t vec, int32_t V,
+                                               float c1, float M2, float invZ, float* w) {
+  constexpr int E = Elems<BF16>::per_vec;
+  float z[E];
+  load_logits<BF16, ALIGNED>(lrow, vec, V, z);
+  float sum = 0.f;
+  if constexpr (RESID) {
+    float q[E];
+    load_probs<E, ALIGNED>(qrow, vec * E, V, q);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      w[e] = fmaxf(0.f, fmaf(fast_exp2(fmaf(z[e], c1, -M2)), invZ, -q[e]));
+      sum += w[e];
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      w[e] = fast_exp2(fmaf(z[e], c1, -M2));
+      sum += w[e];
+    }
+  }
+  return sum;
+}
+
+// Residual mass per chunk of the rejected row, one wave per chunk; sessions that were not
+// rejected exit at once.
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t groups) {
+  constexpr int E = Elems<BF16>::per_vec;
+  const int lane = threadIdx.x & 63;
+  const int32_t b = blockIdx.x / groups;
+  const int32_t c = (blockIdx.x - b * groups) * 4 + (threadIdx.x >> 6);
+  if (c >= a.C || a.skip[b] || !a.rejected[b]) return;
+  const int64_t off0 = session_first_draft(a, b);
+  const int32_t g = a.offsets ? a.offsets[b + 1] - a.offsets[b] : a.gamma;
+  const int32_t n = a.accepted_len[b];
+  if (n < 0 || n >= g) return;   // not the record verify wrote for this batch: touch nothing
+  const int64_t lrow = off0 + b + n;
+  const float2 st = a.row_tab[lrow];
+  const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
+  const float invZ = 1.f / st.y;
+  const char* lp = logits_row<BF16>(a, lrow);
+  const float* qp = a.draft_probs + (off0 + n) * (int64_t)a.V;
+  const int64_t v0 = (int64_t)c * kChunkVecs + lane;
+  float acc = 0.f;
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) {
+    float w[E];
+    acc += group_weights<BF16, ALIGNED, true>(lp, qp, v0 + k * kWave, a.V, c1, st.x, invZ, w);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) a.resid_mass[(int64_t)b * a.C + c] = acc;
+}
+
+// Inverse-CDF draw inside one chunk: target in [0, chunk mass) -> vocabulary index.
+// The wave scans the chunk's 8 sub-blocks of 64 groups; at each level (sub-block, lane, element)
+// the local target is clamped into [0, local total) so that a token is always found and a
+// zero-weight token never is.
+template <bool BF16, bool ALIGNED, bool RESID>
+__device__ __forceinline__ int32_t pick_in_chunk(const char* lp, const float* qp, int32_t V, int32_t c,
+                                                 float c1, float M2, float invZ, float target, int lane) {
+  constexpr int E = Elems<BF16>::per_vec;
+  const int64_t v0 = (int64_t)c * kChunkVecs + lane;
+  float lsum[kUnroll], scan[kUnroll], S[kUnroll];
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) {
+    float w[E];
+    lsum[k] = group_weights<BF16, ALIGNED, RESID>(lp, qp, v0 + k * kWave, V, c1, M2, invZ, w);
+    scan[k] = wave_scan(lsum[k], lane);
+    S[k] = lane_value(scan[k], 63);
+  }
+  float total = 0.f;
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) total += S[k];
+  if (!(total > 0.f)) return -1;
+  float t = fminf(fmaxf(target, 0.f), next_below(total));
+  // sub-block
+  int ksel = kUnroll - 1;
+  float before = 0.f, run = 0.f;
+  bool found = false;
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) {
+    const float upto = run + S[k];
+    if (!found && upto > t) { found = true; ksel = k; before = run; }
+    run = upto;
+  }
+  float my_sum = 0.f, my_scan = 0.f, Ssel = 0.f;
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k)
+    if (k == ksel) { my_sum = lsum[k]; my_scan = scan[k]; Ssel = S[k]; }
+  // lane
+  float t2 = fminf(fmaxf(t - before, 0.f), next_below(Ssel));
+  const uint64_t over = __ballot(my_scan > t2);
+  const int lsel = over ? __ffsll((long long)over) - 1 : 63;
+  const float excl = lsel > 0 ? lane_value(my_scan, lsel - 1) : 0.f;
+  const float sum_sel = lane_value(my_sum, lsel);
+  const float t3 = fminf(fmaxf(t2 - excl, 0.f), next_below(sum_sel));
+  // element: the selected lane recomputes its group
+  int32_t token = -1;
+  if (lane == lsel) {
+    float w[E];
+    const int64_t vec = v0 + (int64_t)ksel * kWave;
+    group_weights<BF16, ALIGNED, RESID>(lp, qp, vec, V, c1, M2, invZ, w);
+    float pre = 0.f;
+    int esel = E - 1;
+    bool hit = false;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      pre += w[e];
+      if (!hit && pre > t3) { hit = true; esel = e; }
+    }
+    token = (int32_t)(vec * E + esel);
+  }
+  return __shfl(token, lsel, kWave);
+}
+
+// Scans per-chunk masses (lane = chunk, batches of 64) and returns the chunk that holds
+// r * total; *target_in_chunk is what is left of r * total once the chunks before it are
+// taken away.  mass(c) must be a pure function of c.  Returns -1 when total is not positive.
+template <typename MassFn>
+__device__ __forceinline__ int32_t pick_chunk(MassFn mass, int32_t C, float r, int lane, float* target_in_chunk,
+                                              float* total_out) {
+  float run = 0.f;
+  for (int32_t base = 0; base < C; base += kWave) {
+    const int32_t c = base + lane;
+    const float sc = wave_scan(c < C ? mass(c) : 0.f, lane);
+    run = run + lane_value(sc, 63);
+  }
+  *total_out = run;
+  if (!(run > 0.f) || !(run < 3.0e38f)) return -1;
+  const float t = fminf(__fmul_rn(r, run), next_below(run));
+  run = 0.f;
+  for (int32_t base = 0; base < C; base += kWave) {
+    const int32_t c = base + lane;
+    const float sc = wave_scan(c < C ? mass(c) : 0.f, lane);
+    const uint64_t over = __ballot((run + sc) > t);
+    if (over) {
+      const int lsel = __ffsll((long long)over) - 1;
+      const float before = lsel > 0 ? run + lane_value(sc, lsel - 1) : run;
+      *target_in_chunk = t - before;
+      return base + lsel;
+    }
+    run = run + lane_value(sc, 63);
+  }
+  *target_in_chunk = 0.f;   // not reachable: the last prefix equals the total, which exceeds t
+  return C - 1;
+}
+
+// One wave per session.  RESID: rejected sessions, row n, weights max(0, P - Q), r = word 1 of
+// the position-n block.  Otherwise: all-accepted sessions, row gamma_b, weights P, r = word 2 of
+// the position-gamma_b block (Algorithm 2: "Sample x_{gamma+1} ~ P_{gamma+1}").
+template <bool BF16, bool ALIGNED, bool RESID>
+__global__ __launch_bounds__(256) void pick_token(const BatchView a) {
+  const int lane = threadIdx.x & 63;
+  const int32_t b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (b >= a.B || a.skip[b]) return;
+  const bool rejected = a.rejected[b] != 0;
+  if (rejected != RESID) return;
+  const int64_t off0 = session_first_draft(a, b);
+  const int32_t g = a.offsets ? a.offsets[b + 1] - a.offsets[b] : a.gamma;
+  const int32_t n = a.accepted_len[b];
+  if (RESID ? (n < 0 || n >= g) : (n != g)) return;   // not verify's record for this batch
+  const int64_t lrow = off0 + b + n;
+  const float2 st = a.row_tab[lrow];
+  const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
+  const float invZ = 1.f / st.y;
+  const char* lp = logits_row<BF16>(a, lrow);
+  const float* qp = RESID ? a.draft_probs + (off0 + n) * (int64_t)a.V : nullptr;
+  const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)n, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi);
+  const float r = u01(rnd.w[RESID ? 1 : 2]);
+
+  const float2* cs = a.chunk_stats + lrow * a.C;
+  auto p_mass = [&](int32_t c) { return cs[c].y * fast_exp2(cs[c].x - st.x); };
+  float target = 0.f, total = 0.f;
+  int32_t token = -1;
+  bool from_p = !RESID;
+  if constexpr (RESID) {
+    const float* rm = a.resid_mass + (int64_t)b * a.C;
+    const int32_t c = pick_chunk([&](int32_t cc) { return rm[cc]; }, a.C, r, lane, &target, &total);
+    if (c >= 0) token = pick_in_chunk<BF16, ALIGNED, true>(lp, qp, a.V, c, c1, st.x, invZ, target, lane);
+    if (token < 0) from_p = true;   // residual mass rounded to zero: draw from P_n instead
+  }
+  if (from_p) {
+    const int32_t c = pick_chunk(p_mass, a.C, r, lane, &target, &total);
+    if (c >= 0) token = pick_in_chunk<BF16, ALIGNED, false>(lp, nullptr, a.V, c, c1, st.x, invZ, target, lane);
+  }
+  if (lane == 0) {
+    a.out_token[b] = token;
+    if (a.status) {
+      if (RESID && from_p) a.status[b] |= 2;
+      if (token < 0) a.status[b] |= 8;
+    }
+  }
+}
+
+}  // namespace dssd

@@ -1,0 +1,125 @@
+"""Shared helpers of the GPU-vs-oracle parity tests: run the CPU oracle over a batch (split
+over host threads by session; each session is still computed by the single-threaded oracle
+code) and compare it with what the HIP library wrote, under the near-tie rule.
+
+Near-tie rule: a decision is a near-tie when the oracle's uniform lies within 1e-5 of the
+decision boundary (|r - p/q| < 1e-5 for an accept test, distance to a CDF boundary below
+1e-5 of the total mass for an inverse-CDF draw).  Near-ties are counted and reported; a
+session with an accept near-tie is left out of the exact comparison, a session with only a
+draw near-tie still has accepted_len and rejected compared exactly.
+"""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+from oracle import oracle as O
+
+TIE = 1e-5
+
+
+def to_numpy_inputs(inputs):
+    """Host copies of a synth batch, logits as the oracle wants them (fp32 or bf16 bits)."""
+    import torch
+    lg = inputs["logits"]
+    if lg.dtype == torch.bfloat16:
+        logits = lg.view(torch.int16).cpu().numpy().view(np.uint16)
+        dtype = O.BF16
+    else:
+        logits = lg.cpu().numpy()
+        dtype = O.F32
+    off = inputs.get("draft_offsets")
+    it = inputs.get("inv_temperature")
+    return dict(logits=logits, dtype=dtype, draft_probs=inputs["draft_probs"].cpu().numpy(),
+                draft_tokens=inputs["draft_tokens"].cpu().numpy(),
+                draft_offsets=None if off is None else off.cpu().numpy(),
+                inv_temperature=None if it is None else it.cpu().numpy(),
+                B=inputs["B"], V=inputs["V"], gamma=inputs["gamma"])
+
+
+def run_oracle(h, seed, step, session_base=0, workers=8, sessions=None):
+    """Oracle results for sessions `sessions` (default: all) of host batch `h`.
+    Returns dict of arrays indexed like the full batch (untouched entries are NaN / -9)."""
+    B, V, gamma = h["B"], h["V"], h["gamma"]
+    off = h["draft_offsets"]
+    if off is None:
+        off = (np.arange(B + 1, dtype=np.int64) * gamma).astype(np.int32)
+    R_Q = int(off[-1]); R_L = R_Q + B
+    res = np.zeros(B, dtype=O.RESULT_DTYPE); res["n"] = -9
+    p_tok = np.full(R_Q, np.nan); q_tok = np.full(R_Q, np.nan); r_acc = np.full(R_Q, np.nan)
+    row_m = np.full(R_L, np.nan); row_Z = np.full(R_L, np.nan)
+    todo = np.arange(B) if sessions is None else np.asarray(sessions)
+
+    def one(b):
+        q0, q1 = int(off[b]), int(off[b + 1])
+        l0, l1 = q0 + b, q1 + b + 1
+        it = None if h["inv_temperature"] is None else h["inv_temperature"][b:b + 1]
+        o = O.verify_batch(h["logits"][l0:l1], h["dtype"], h["draft_probs"][q0:q1],
+                           h["draft_tokens"][q0:q1], V, gamma=q1 - q0,
+                           draft_offsets=np.array([0, q1 - q0], np.int32),
+                           inv_temperature=it, seed=seed, step=step, session_base=session_base + b)
+        res[b] = o["res"][0]
+        p_tok[q0:q1] = o["p_tok"]; q_tok[q0:q1] = o["q_tok"]; r_acc[q0:q1] = o["r_acc"]
+        row_m[l0:l1] = o["row_m"]; row_Z[l0:l1] = o["row_Z"]
+
+    if workers > 1 and len(todo) > 1:
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(one, todo))
+    else:
+        for b in todo:
+            one(b)
+    return dict(res=res, p_tok=p_tok, q_tok=q_tok, r_acc=r_acc, row_m=row_m, row_Z=row_Z,
+                offsets=off, sessions=todo)
+
+
+def compare(h, gpu, orc, p_rtol):
+    """gpu: dict of numpy arrays (accepted_len, rejected, out_token, row_stats, p_tok, q_tok,
+    status).  Returns a report dict; raises AssertionError on a mismatch outside near-ties."""
+    off = orc["offsets"]
+    res = orc["res"]
+    rep = dict(sessions=0, accept_ties=0, draw_ties=0, positions=0, max_p_rel=0.0, max_lse_abs=0.0,
+               rejected=0)
+    bad = []
+    for b in orc["sessions"]:
+        b = int(b)
+        q0, q1 = int(off[b]), int(off[b + 1])
+        l0, l1 = q0 + b, q1 + b + 1
+        r = res[b]
+        rep["sessions"] += 1
+        rep["positions"] += q1 - q0
+        # input-fault bits must agree; the zero-residual bit (2) can only differ in a near-tie
+        assert (int(gpu["status"][b]) & ~2) == (int(r["status"]) & ~2), (b, gpu["status"][b], r["status"])
+        if r["status"] & 1:
+            assert gpu["accepted_len"][b] == 0 and gpu["rejected"][b] == 1 and gpu["out_token"][b] == -1
+            continue
+        # probabilities at every draft position, statistics of every row
+        po, pg = orc["p_tok"][q0:q1], gpu["p_tok"][q0:q1].astype(np.float64)
+        big = po > 1e-30
+        if big.any():
+            rel = np.abs(pg[big] - po[big]) / po[big]
+            rep["max_p_rel"] = max(rep["max_p_rel"], float(rel.max()))
+        assert (np.abs(pg[~big]) <= 1e-30 * (1 + p_rtol)).all()
+        assert (gpu["q_tok"][q0:q1].astype(np.float64) == orc["q_tok"][q0:q1]).all(), b
+        lse_o = orc["row_m"][l0:l1] + np.log(orc["row_Z"][l0:l1])
+        rs = gpu["row_stats"][l0:l1].astype(np.float64)
+        lse_g = rs[:, 0] + np.log(rs[:, 1])
+        rep["max_lse_abs"] = max(rep["max_lse_abs"], float(np.abs(lse_g - lse_o).max()))
+        # decisions
+        rep["rejected"] += int(r["rejected"])
+        if r["accept_margin"] < TIE:
+            rep["accept_ties"] += 1
+            continue
+        if gpu["accepted_len"][b] != r["n"] or gpu["rejected"][b] != r["rejected"]:
+            bad.append((b, "n", int(gpu["accepted_len"][b]), int(r["n"])))
+            continue
+        if r["cdf_margin"] < TIE:
+            rep["draw_ties"] += 1
+            assert 0 <= gpu["out_token"][b] < h["V"]
+            continue
+        if gpu["out_token"][b] != r["token"]:
+            bad.append((b, "token", int(gpu["out_token"][b]), int(r["token"]), float(r["cdf_margin"])))
+    assert not bad, f"{len(bad)} mismatches outside near-ties, first: {bad[:5]}"
+    assert rep["max_p_rel"] <= p_rtol, rep
+    assert rep["max_lse_abs"] <= p_rtol, rep
+    ties = rep["accept_ties"] + rep["draw_ties"]
+    assert ties <= max(2, 2e-3 * (rep["positions"] + rep["sessions"])), rep
+    return rep

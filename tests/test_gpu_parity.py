@@ -1,0 +1,191 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Bit-exact accepted_len / rejected / out_token outside counted
+near-ties; p_i(x_i) and the row log-sum-exp within 1e-5 (fp32 logits) or 2e-3 (bf16 logits)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2507_12000_amd import binding as D   # noqa: E402
+from paper_2507_12000_amd import synth          # noqa: E402
+import parity                                   # noqa: E402
+
+DEV = "cuda:0"
+P_RTOL = {"f32": 1e-5, "bf16": 2e-3}
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = D.Context(DEV, max_rows=10240, max_V=262144)
+    yield c
+    c.close()
+
+
+def gpu_step(ctx, inputs, seed, step, session_base=0):
+    batch = D.make_batch(inputs, seed=seed, step=step, session_base=session_base)
+    t, out = D.alloc_out(inputs, DEV)
+    ctx.step(batch, out)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in t.items()}
+
+
+def check(ctx, w, seed=0, step=0, sessions=None, workers=16, gen_seed=0):
+    print(f"[parity] {w.name} B={w.B} V={w.V} seed={seed} step={step}", flush=True)
+    inputs = synth.generate(w, seed=gen_seed, device=DEV)
+    gpu = gpu_step(ctx, inputs, seed, step)
+    h = parity.to_numpy_inputs(inputs)
+    orc = parity.run_oracle(h, seed, step, workers=workers, sessions=sessions)
+    rep = parity.compare(h, gpu, orc, P_RTOL[w.dtype])
+    print(f"[parity] {w.name}: {rep}", flush=True)
+    return inputs, gpu, orc, rep
+
+
+SMALL = [
+    # several chunks plus a ragged tail, aligned rows
+    synth.Workload("f32_aligned_tail", B=9, V=10000, gamma=3, dtype="f32"),
+    synth.Workload("bf16_aligned_tail", B=9, V=4096 * 2 + 8, gamma=5, dtype="bf16", sigmas=(1.0,)),
+    # rows that are not 16-byte aligned: scalar loads
+    synth.Workload("f32_unaligned", B=7, V=9999, gamma=2, dtype="f32"),
+    synth.Workload("bf16_unaligned", B=7, V=12345, gamma=4, dtype="bf16"),
+    # one chunk, smaller than a wave's share
+    synth.Workload("f32_tiny_V", B=5, V=37, gamma=2, dtype="f32", zipf_s=0.5),
+    synth.Workload("bf16_V1", B=3, V=1, gamma=2, dtype="bf16"),
+    # ragged gammas with temperature and every session class
+    synth.Workload("bf16_ragged_temp", B=41, V=20000, gamma=0, dtype="bf16", gamma_range=(1, 16),
+                   temperature_range=(0.5, 1.5), sigmas=(0.25, 2.0), frac_q_equals_p=0.2,
+                   frac_q_uniform=0.2),
+    synth.Workload("f32_ragged", B=33, V=5000, gamma=0, dtype="f32", gamma_range=(0, 7), sigmas=(2.0,)),
+    # more than 64 chunks per row (fp32 chunk = 2048 entries)
+    synth.Workload("f32_many_chunks", B=3, V=2048 * 70 + 12, gamma=2, dtype="f32", sigmas=(2.0,)),
+    # gamma above one wave of positions
+    synth.Workload("f32_long_gamma", B=2, V=300, gamma=70, dtype="f32", sigmas=(0.1,)),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=[w.name for w in SMALL])
+def test_small_shapes(ctx, w):
+    for step in (0, 1):
+        check(ctx, w, seed=1234, step=step, workers=4)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_benchmark_workloads_full(ctx, idx):
+    inputs, gpu, orc, rep = check(ctx, synth.WORKLOADS[idx], seed=0, step=0)
+    assert rep["sessions"] == synth.WORKLOADS[idx].B
+
+
+def test_workload0_many_steps(ctx):
+    """Workload 0 is defined as repeated verify steps on one session: vary the step counter."""
+    w = synth.WORKLOADS[0]
+    inputs = synth.generate(w, seed=0, device=DEV)
+    h = parity.to_numpy_inputs(inputs)
+    n_hist = np.zeros(w.gamma + 1, int)
+    for step in range(40):
+        gpu = gpu_step(ctx, inputs, 7, step)
+        orc = parity.run_oracle(h, 7, step, workers=1)
+        parity.compare(h, gpu, orc, 1e-5)
+        n_hist[gpu["accepted_len"][0]] += 1
+    assert (n_hist > 0).sum() >= 2       # the random stream really depends on the step
+
+
+@pytest.mark.parametrize("idx,stride", [(3, 1), (4, 1)])
+def test_benchmark_workloads_large(ctx, idx, stride):
+    """Full-size launch; the oracle checks every `stride`-th session."""
+    w = synth.WORKLOADS[idx]
+    sessions = np.arange(0, w.B, stride)
+    inputs, gpu, orc, rep = check(ctx, w, seed=0, step=3, sessions=sessions)
+    # properties that hold for every session, whatever the oracle sampled
+    gam = np.diff(orc["offsets"])
+    n, rej, tok = gpu["accepted_len"], gpu["rejected"], gpu["out_token"]
+    assert ((n >= 0) & (n <= gam)).all() and ((rej == 1) == (n < gam)).all()
+    assert ((tok >= 0) & (tok < w.V)).all() and (gpu["status"] & ~2 == 0).all()
+    cls = inputs["session_class"].cpu().numpy()
+    if (cls == 1).any():
+        assert (n[cls == 1] == gam[cls == 1]).mean() > 0.95
+        assert n[cls == 2].mean() < 1.0
+
+
+def test_determinism_and_shard_independence(ctx):
+    w = synth.Workload("shard", B=24, V=6000, gamma=4, dtype="bf16", sigmas=(1.0,))
+    inputs = synth.generate(w, seed=5, device=DEV)
+    a = gpu_step(ctx, inputs, 9, 2)
+    b = gpu_step(ctx, inputs, 9, 2)
+    for k in a:
+        assert (a[k] == b[k]).all(), k
+    # the second half of the batch run on its own, with its global session ids
+    half = w.B // 2
+    g = w.gamma
+    sub = dict(inputs)
+    sub.update(B=half, R_Q=half * g, R_L=half * (g + 1),
+               logits=inputs["logits"][half * (g + 1):].contiguous(),
+               draft_probs=inputs["draft_probs"][half * g:].contiguous(),
+               draft_tokens=inputs["draft_tokens"][half * g:].contiguous())
+    c = gpu_step(ctx, sub, 9, 2, session_base=half)
+    for k in ("accepted_len", "rejected", "out_token"):
+        assert (c[k] == a[k][half:]).all(), k
+    d = gpu_step(ctx, inputs, 9, 3)
+    assert (d["out_token"] != a["out_token"]).any()
+
+
+def test_degenerate_sessions(ctx):
+    V, g = 5000, 3
+    dev = torch.device(DEV)
+    gen = torch.Generator(device=dev); gen.manual_seed(3)
+    B = 6
+    z = torch.randn((B * (g + 1), V), generator=gen, device=dev)
+    P = torch.softmax(z.double(), 1)
+    Q = torch.empty((B * g, V), device=dev)
+    tok = torch.randint(0, V, (B * g,), generator=gen, device=dev, dtype=torch.int32)
+    for b in range(B):
+        for i in range(g):
+            Q[b * g + i] = torch.nextafter(P[b * (g + 1) + i].float(), torch.zeros((), device=dev))
+    # session 1: one-hot draft on a token the target gives ~0 -> reject at 0
+    z[1 * (g + 1), 7] = -80.0
+    Q[1 * g] = 0; Q[1 * g, 7] = 1.0; tok[1 * g] = 7
+    # session 2: last vocabulary entry as draft, session 3: a token id out of range
+    tok[2 * g + 1] = V - 1
+    tok[3 * g + 2] = V
+    # session 4: q = 0 at the draft token (p > 0 accepts)
+    Q[4 * g, int(tok[4 * g])] = 0.0
+    inputs = dict(logits=z.contiguous(), draft_probs=Q, draft_tokens=tok, draft_offsets=None,
+                  inv_temperature=None, B=B, V=V, gamma=g, R_L=B * (g + 1), R_Q=B * g)
+    gpu = gpu_step(ctx, inputs, 77, 0)
+    h = parity.to_numpy_inputs(inputs)
+    orc = parity.run_oracle(h, 77, 0, workers=1)
+    parity.compare(h, gpu, orc, 1e-5)
+    assert (gpu["accepted_len"][[0, 2, 4, 5]] == g).all() and (gpu["rejected"][[0, 2, 4, 5]] == 0).all()
+    assert gpu["accepted_len"][1] == 0 and gpu["rejected"][1] == 1 and gpu["out_token"][1] != 7
+    assert gpu["status"][3] == D.SESSION_BAD_TOKEN and gpu["out_token"][3] == -1
+
+
+def test_empty_batch_gamma_zero_and_errors(ctx):
+    w = synth.Workload("g0", B=4, V=3000, gamma=0, dtype="f32")
+    inputs = synth.generate(w, seed=1, device=DEV)
+    gpu = gpu_step(ctx, inputs, 5, 0)          # gamma = 0: only bonus tokens
+    h = parity.to_numpy_inputs(inputs)
+    orc = parity.run_oracle(h, 5, 0, workers=1)
+    parity.compare(h, gpu, orc, 1e-5)
+    assert (gpu["accepted_len"] == 0).all() and (gpu["rejected"] == 0).all()
+    # B = 0 is a no-op
+    batch = D.make_batch(inputs, seed=1)
+    t, out = D.alloc_out(inputs, DEV)
+    batch.B = 0; batch.total_drafts = 0
+    for f in (D.dssd_verify_batch, D.dssd_residual_sample, D.dssd_bonus_sample):
+        assert f(ctx.handle, batch, out, ctx.stream(), check=False) == D.DSSD_OK
+    torch.cuda.synchronize()
+    assert (t["accepted_len"].cpu().numpy() == -7).all()
+    # host-checkable errors
+    batch = D.make_batch(inputs, seed=1)
+    batch.V = 262145
+    assert D.dssd_verify_batch(ctx.handle, batch, out, 0, check=False) == D.DSSD_ENOMEM
+    batch = D.make_batch(inputs, seed=1); batch.logits = None
+    assert D.dssd_verify_batch(ctx.handle, batch, out, 0, check=False) == D.DSSD_EINVAL
+    batch = D.make_batch(inputs, seed=1); batch.logits = inputs["logits"].data_ptr() + 2
+    assert D.dssd_verify_batch(ctx.handle, batch, out, 0, check=False) == D.DSSD_EALIGN
+    batch = D.make_batch(inputs, seed=1); batch.total_drafts = 3
+    assert D.dssd_verify_batch(ctx.handle, batch, out, 0, check=False) == D.DSSD_EINVAL
+    batch = D.make_batch(inputs, seed=1); batch.logits_dtype = 9
+    assert D.dssd_bonus_sample(ctx.handle, batch, out, 0, check=False) == D.DSSD_EINVAL
+    torch.cuda.synchronize()
