@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSSD verification step on one MI355X.
+
+A "step" is one pass of the whole hot path -- dssd_verify_batch, dssd_residual_sample,
+dssd_bonus_sample back to back on one stream -- over one synthetic batch that is already
+resident in HBM.  Prints ONE JSON line:  verified draft positions per second for the whole
+step, the HBM roofline figure of the dominant kernel (the row softmax statistics, timed with
+HIP events on the launch stream inside the timed region), and the CPU oracle timed on a
+bounded sample of the same batch (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(inputs, rejected, C_bonus_fraction):
+    """Bytes the method must move in one step: every logits row once; for each rejected
+    session its P row again plus its Q row; for each accepted session one chunk of the bonus
+    row; the per-position gathers; the result records."""
+    V, B, R_L, R_Q = inputs["V"], inputs["B"], inputs["R_L"], inputs["R_Q"]
+    s_L = inputs["logits"].element_size()
+    n_rej = int(rejected.sum())
+    stats = R_L * V * s_L
+    resid = n_rej * V * (s_L + 4)
+    bonus = (B - n_rej) * V * s_L * C_bonus_fraction
+    gathers = R_Q * (4 + 4 + s_L)
+    return dict(row_stats=stats, residual=resid, bonus=bonus, gathers=gathers, records=12 * B,
+                total=stats + resid + bonus + gathers + 12 * B)
+
+
+def cpu_baseline(inputs, seed, budget_s=12.0):
+    """Time the oracle, as it stands, single-threaded, on the first sessions of the batch."""
+    import numpy as np
+    import torch
+    import parity
+    from oracle import oracle as O
+    B = inputs["B"]
+    off = inputs["draft_offsets"]
+    off = (np.arange(B + 1) * inputs["gamma"]) if off is None else off.cpu().numpy().astype(np.int64)
+
+    def host_slice(b0, b1):
+        q0, q1 = int(off[b0]), int(off[b1])
+        sub = dict(inputs)
+        sub.update(B=b1 - b0, R_Q=q1 - q0, R_L=q1 - q0 + b1 - b0,
+                   logits=inputs["logits"][q0 + b0:q1 + b1], draft_probs=inputs["draft_probs"][q0:q1],
+                   draft_tokens=inputs["draft_tokens"][q0:q1],
+                   draft_offsets=None if inputs["draft_offsets"] is None
+                   else (inputs["draft_offsets"][b0:b1 + 1] - int(off[b0])),
+                   inv_temperature=None if inputs["inv_temperature"] is None
+                   else inputs["inv_temperature"][b0:b1])
+        return parity.to_numpy_inputs(sub), q1 - q0
+
+    def run(h):
+        t0 = time.perf_counter()
+        O.verify_batch(h["logits"], h["dtype"], h["draft_probs"], h["draft_tokens"], h["V"],
+                       gamma=h["gamma"], draft_offsets=h["draft_offsets"],
+                       inv_temperature=h["inv_temperature"], seed=seed, step=0)
+        return time.perf_counter() - t0
+
+    h1, pos1 = host_slice(0, 1)
+    run(h1)                                   # page in, warm the caches
+    t1 = max(run(h1), 1e-6)
+    per_pos = t1 / max(pos1, 1)
+    n = 1
+    while n < B and per_pos * int(off[n]) < budget_s:
+        n += 1
+    h, pos = host_slice(0, n)
+    t = run(h)
+    return {"value": pos / t, "unit": "positions/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n} of {B} sessions ({pos} draft positions), one thread, {t:.2f} s",
+            "rows_per_s": (pos + n) / t}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="index into the five benchmark workloads")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run a plain device copy of known size instead (calibrates the HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the verification step shards by session with no "
+              "collective, and no multi-GPU run is part of this benchmark (use --gpus 1).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_12000_amd import binding as D, synth
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    if args.copy_probe:
+        # 2 GiB read + 2 GiB written per launch by torch's elementwise copy kernel
+        n = 1 << 30
+        src = torch.arange(n, device=dev, dtype=torch.int16)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 10
+        print(json.dumps({"copy_probe": True, "bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n,
+                          "launches": 10, "GBps_read_plus_write": 4 * n / dt / 1e9}))
+        return
+    w = synth.WORKLOADS[args.config]
+    inputs = synth.generate(w, seed=args.seed, device=dev)
+    torch.cuda.synchronize()
+    ctx = D.Context(dev, max_rows=inputs["R_L"], max_V=w.V)
+    batch = D.make_batch(inputs, seed=args.seed, step=0)
+    outs, out = D.alloc_out(inputs, dev, debug=False)
+
+    for k in range(args.warmup):
+        batch.step = k
+        ctx.step(batch, out)
+    torch.cuda.synchronize()
+    D.dssd_profile_reset(ctx.handle)
+    D.dssd_profile_enable(ctx.handle, True)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        batch.step = args.warmup + k
+        ctx.step(batch, out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    D.dssd_profile_enable(ctx.handle, False)
+
+    kernels = {}
+    for k in range(D.K_COUNT):
+        ms, n = D.dssd_profile_read(ctx.handle, k)
+        kernels[D.kernel_name(k)] = {"avg_us": 1e3 * ms / max(n, 1), "launches": n}
+    rejected = outs["rejected"].cpu().numpy()
+    s_L = inputs["logits"].element_size()
+    chunk_elems = 4096 if s_L == 2 else 2048
+    C = -(-w.V // chunk_elems)
+    ab = algorithmic_bytes(inputs, rejected, 1.0 / C)
+    ms_per_step = 1e3 * elapsed / args.steps
+    k1_us = kernels["row_chunk_stats"]["avg_us"]
+    achieved = ab["row_stats"] / (k1_us * 1e-6) / 1e9
+    result = {
+        "metric": "verified_draft_positions_per_sec",
+        "value": inputs["R_Q"] * args.steps / elapsed,
+        "unit": "positions/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "V": w.V, "logits_dtype": w.dtype,
+                   "logits_rows": inputs["R_L"], "draft_positions": inputs["R_Q"],
+                   "rejected_sessions": int(rejected.sum())},
+        "vocab_rows_per_sec": inputs["R_L"] * args.steps / elapsed,
+        "step_algorithmic_GBps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernels": kernels,
+        "roofline": {"bound": "hbm", "kernel": "row_chunk_stats", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": ab["row_stats"],
+                     "avg_launch_us": k1_us},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(inputs, args.seed, budget_s=15.0)
+    ctx.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

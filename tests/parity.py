@@ -71,13 +71,36 @@ def run_oracle(h, seed, step, session_base=0, workers=8, sessions=None):
                 offsets=off, sessions=todo)
 
 
-def compare(h, gpu, orc, p_rtol):
+def _draw_is_valid(h, orc, b, token, seed, step, session_base):
+    """For a draw the oracle flags as a near-tie: is `token` a correct answer once the target
+    r * total may move by 1e-5 of the total mass?  Recomputed from the oracle's pieces."""
+    off = orc["offsets"]
+    r = orc["res"][b]
+    n = int(r["n"])
+    lrow = int(off[b]) + b + n
+    tau = 1.0 if h["inv_temperature"] is None else float(h["inv_temperature"][b])
+    P = O.softmax_row(h["logits"][lrow], h["dtype"], tau)[0]
+    words = O.random_block(seed, step, session_base + b, n)
+    if r["rejected"] and not (r["status"] & 2):
+        w, _ = O.residual(P, h["draft_probs"][int(off[b]) + n])
+        u = O.u01(words[1])
+    else:
+        w, u = P, O.u01(words[1] if r["rejected"] else words[2])
+    c = np.cumsum(w)
+    t, R = u * c[-1], c[-1]
+    lo = c[token - 1] if token > 0 else 0.0
+    return w[token] > 0 and lo - TIE * R <= t < c[token] + TIE * R
+
+
+def compare(h, gpu, orc, p_rtol, seed=None, step=None, session_base=0):
     """gpu: dict of numpy arrays (accepted_len, rejected, out_token, row_stats, p_tok, q_tok,
-    status).  Returns a report dict; raises AssertionError on a mismatch outside near-ties."""
+    status).  Returns a report dict; raises AssertionError on a mismatch outside near-ties.
+    Where the two sides differ inside a near-tie the GPU's answer must still be a valid one
+    (checked when seed and step are given)."""
     off = orc["offsets"]
     res = orc["res"]
-    rep = dict(sessions=0, accept_ties=0, draw_ties=0, positions=0, max_p_rel=0.0, max_lse_abs=0.0,
-               rejected=0)
+    rep = dict(sessions=0, positions=0, rejected=0, accept_ties=0, draw_ties=0,
+               accept_tie_differs=0, draw_tie_differs=0, max_p_rel=0.0, max_lse_abs=0.0)
     bad = []
     for b in orc["sessions"]:
         b = int(b)
@@ -105,21 +128,26 @@ def compare(h, gpu, orc, p_rtol):
         rep["max_lse_abs"] = max(rep["max_lse_abs"], float(np.abs(lse_g - lse_o).max()))
         # decisions
         rep["rejected"] += int(r["rejected"])
-        if r["accept_margin"] < TIE:
-            rep["accept_ties"] += 1
+        accept_tie = r["accept_margin"] < TIE
+        draw_tie = r["cdf_margin"] < TIE
+        rep["accept_ties"] += int(accept_tie)
+        rep["draw_ties"] += int(draw_tie)
+        g_n, g_rej, g_tok = int(gpu["accepted_len"][b]), int(gpu["rejected"][b]), int(gpu["out_token"][b])
+        assert 0 <= g_n <= q1 - q0 and g_rej == int(g_n < q1 - q0) and 0 <= g_tok < h["V"], (b, g_n, g_rej, g_tok)
+        if g_n != r["n"] or g_rej != r["rejected"]:
+            if accept_tie:
+                rep["accept_tie_differs"] += 1
+            else:
+                bad.append((b, "n", g_n, int(r["n"]), float(r["accept_margin"])))
             continue
-        if gpu["accepted_len"][b] != r["n"] or gpu["rejected"][b] != r["rejected"]:
-            bad.append((b, "n", int(gpu["accepted_len"][b]), int(r["n"])))
-            continue
-        if r["cdf_margin"] < TIE:
-            rep["draw_ties"] += 1
-            assert 0 <= gpu["out_token"][b] < h["V"]
-            continue
-        if gpu["out_token"][b] != r["token"]:
-            bad.append((b, "token", int(gpu["out_token"][b]), int(r["token"]), float(r["cdf_margin"])))
+        if g_tok != r["token"]:
+            if draw_tie and (seed is None or _draw_is_valid(h, orc, b, g_tok, seed, step, session_base)):
+                rep["draw_tie_differs"] += 1
+            else:
+                bad.append((b, "token", g_tok, int(r["token"]), float(r["cdf_margin"])))
     assert not bad, f"{len(bad)} mismatches outside near-ties, first: {bad[:5]}"
     assert rep["max_p_rel"] <= p_rtol, rep
     assert rep["max_lse_abs"] <= p_rtol, rep
-    ties = rep["accept_ties"] + rep["draw_ties"]
-    assert ties <= max(2, 2e-3 * (rep["positions"] + rep["sessions"])), rep
+    differs = rep["accept_tie_differs"] + rep["draw_tie_differs"]
+    assert differs <= max(2, 1e-3 * (rep["positions"] + rep["sessions"])), rep
     return rep

@@ -37,7 +37,7 @@ def check(ctx, w, seed=0, step=0, sessions=None, workers=16, gen_seed=0):
     gpu = gpu_step(ctx, inputs, seed, step)
     h = parity.to_numpy_inputs(inputs)
     orc = parity.run_oracle(h, seed, step, workers=workers, sessions=sessions)
-    rep = parity.compare(h, gpu, orc, P_RTOL[w.dtype])
+    rep = parity.compare(h, gpu, orc, P_RTOL[w.dtype], seed=seed, step=step)
     print(f"[parity] {w.name}: {rep}", flush=True)
     return inputs, gpu, orc, rep
 
@@ -85,7 +85,7 @@ def test_workload0_many_steps(ctx):
     for step in range(40):
         gpu = gpu_step(ctx, inputs, 7, step)
         orc = parity.run_oracle(h, 7, step, workers=1)
-        parity.compare(h, gpu, orc, 1e-5)
+        parity.compare(h, gpu, orc, 1e-5, seed=7, step=step)
         n_hist[gpu["accepted_len"][0]] += 1
     assert (n_hist > 0).sum() >= 2       # the random stream really depends on the step
 
@@ -154,7 +154,7 @@ def test_degenerate_sessions(ctx):
     gpu = gpu_step(ctx, inputs, 77, 0)
     h = parity.to_numpy_inputs(inputs)
     orc = parity.run_oracle(h, 77, 0, workers=1)
-    parity.compare(h, gpu, orc, 1e-5)
+    parity.compare(h, gpu, orc, 1e-5, seed=77, step=0)
     assert (gpu["accepted_len"][[0, 2, 4, 5]] == g).all() and (gpu["rejected"][[0, 2, 4, 5]] == 0).all()
     assert gpu["accepted_len"][1] == 0 and gpu["rejected"][1] == 1 and gpu["out_token"][1] != 7
     assert gpu["status"][3] == D.SESSION_BAD_TOKEN and gpu["out_token"][3] == -1
@@ -166,7 +166,7 @@ def test_empty_batch_gamma_zero_and_errors(ctx):
     gpu = gpu_step(ctx, inputs, 5, 0)          # gamma = 0: only bonus tokens
     h = parity.to_numpy_inputs(inputs)
     orc = parity.run_oracle(h, 5, 0, workers=1)
-    parity.compare(h, gpu, orc, 1e-5)
+    parity.compare(h, gpu, orc, 1e-5, seed=5, step=0)
     assert (gpu["accepted_len"] == 0).all() and (gpu["rejected"] == 0).all()
     # B = 0 is a no-op
     batch = D.make_batch(inputs, seed=1)
