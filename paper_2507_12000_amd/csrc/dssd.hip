@@ -177,7 +177,7 @@ extern "C" dssd_status dssd_verify_batch(dssd_ctx* c, const dssd_batch* b, dssd_
   }
   {
     Timed t(c, DSSD_K_ACCEPT, s);
-    const unsigned g2 = (unsigned)((b->B + 3) / 4);
+    const unsigned g2 = (unsigned)b->B;   // one workgroup per session
     if (bf16) DSSD_LAUNCH((accept_scan<true>), g2, s, v); else DSSD_LAUNCH((accept_scan<false>), g2, s, v);
   }
   return launch_status();

@@ -84,27 +84,31 @@ __device__ __forceinline__ float wave_scan(float x, int lane) {
 // ------------------------------------------------------------------ row access
 // Loads the `vec`-th group of per_vec consecutive logits of a row as floats.  Entries at or
 // beyond V read as -inf.  ALIGNED: the row starts on a 16-byte boundary and V is a multiple of
-// per_vec, so the group is one 128-bit load.
+// per_vec, so the group is one 128-bit load; it is issued non-temporal (the rows are streamed
+// once and far exceed the caches) and without a branch (the address is clamped into the row,
+// the value replaced afterwards).
 template <bool BF16, bool ALIGNED>
 __device__ __forceinline__ void load_logits(const void* row, int64_t vec, int32_t V, float* z) {
   constexpr int E = Elems<BF16>::per_vec;
   const int64_t e0 = vec * E;
   if constexpr (ALIGNED) {
-    if (e0 < V) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(static_cast<const char*>(row) + vec * 16);
-      if constexpr (BF16) {
+    const int64_t last = V / E - 1;
+    const bool inside = vec <= last;
+    const u32x4* p = reinterpret_cast<const u32x4*>(row) + (inside ? vec : last);
+    u32x4 v = __builtin_nontemporal_load(p);
+    if (!inside) {
+      const uint32_t ninf = BF16 ? 0xFF80FF80u : 0xFF800000u;
+      v = (u32x4){ninf, ninf, ninf, ninf};
+    }
+    if constexpr (BF16) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          z[2 * i] = as_float(v[i] << 16);
-          z[2 * i + 1] = as_float(v[i] & 0xFFFF0000u);
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) z[i] = as_float(v[i]);
+      for (int i = 0; i < 4; ++i) {
+        z[2 * i] = as_float(v[i] << 16);
+        z[2 * i + 1] = as_float(v[i] & 0xFFFF0000u);
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < E; ++i) z[i] = neg_inf();
+      for (int i = 0; i < 4; ++i) z[i] = as_float(v[i]);
     }
   } else {
 #pragma unroll
@@ -123,24 +127,32 @@ __device__ __forceinline__ float load_logit(const void* row, int64_t e, bool bf1
   return bf16 ? as_float((uint32_t) static_cast<const uint16_t*>(row)[e] << 16)
               : static_cast<const float*>(row)[e];
 }
-// Loads draft probabilities [e0, e0+N) of a row; entries at or beyond V read as 0.
+// Loads draft probabilities [e0, e0+N) of a row (N = 4 or 8, e0 a multiple of N); entries at
+// or beyond V read as 0.  ALIGNED as above: non-temporal 128-bit loads, clamped, no branch.
 template <int N, bool ALIGNED>
 __device__ __forceinline__ void load_probs(const float* row, int64_t e0, int32_t V, float* q) {
   if constexpr (ALIGNED) {
-    if (e0 < V) {
+    const bool inside = e0 < V;
+    const f32x4* p = reinterpret_cast<const f32x4*>(row + (inside ? e0 : (int64_t)V - N));
 #pragma unroll
-      for (int i = 0; i < N / 4; ++i) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(row + e0 + 4 * i);
-        q[4 * i] = v[0]; q[4 * i + 1] = v[1]; q[4 * i + 2] = v[2]; q[4 * i + 3] = v[3];
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < N; ++i) q[i] = 0.f;
+    for (int i = 0; i < N / 4; ++i) {
+      const f32x4 v = __builtin_nontemporal_load(p + i);
+      q[4 * i] = inside ? v[0] : 0.f; q[4 * i + 1] = inside ? v[1] : 0.f;
+      q[4 * i + 2] = inside ? v[2] : 0.f; q[4 * i + 3] = inside ? v[3] : 0.f;
     }
   } else {
 #pragma unroll
     for (int i = 0; i < N; ++i) q[i] = (e0 + i < V) ? row[e0 + i] : 0.f;
   }
+}
+
+// Consecutive workgroup ids are dealt round-robin to the chip's 8 XCDs.  This maps a hardware
+// workgroup id to a logical one so that each XCD walks one contiguous eighth of the work (and
+// of the address range) instead of every eighth block of it.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int64_t xcd_contiguous(int64_t block, int64_t blocks) {
+  const int64_t per = blocks / kXcds;
+  return block < per * kXcds ? (block % kXcds) * per + block / kXcds : block;
 }
 
 }  // namespace dssd

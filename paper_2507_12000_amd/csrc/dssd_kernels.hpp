@@ -5,8 +5,8 @@
 //
 //   row_chunk_stats : per chunk, m2_c = max(z) * c1 and s_c = sum 2^(z*c1 - m2_c), with
 //                     c1 = log2(e)/T.  One exp per element, no cross-wave traffic.
-//   accept_scan     : per session, merges the chunk pairs into row (M2, Z), gathers p_i(x_i) and
-//                     q_i(x_i), draws r_i, and finds the first rejected draft with a ballot.
+//   accept_scan     : per session (one workgroup), merges the chunk pairs into row (M2, Z), gathers
+//                     p_i(x_i) and q_i(x_i), draws r_i, finds the first rejected draft with a ballot.
 //   resid_mass      : per chunk of the rejected row, the mass of max(0, P - Q).
 //   resid_pick / bonus_pick : scan the chunk masses, then re-read the one chunk that holds
 //                     r * total and locate the token by a wave prefix sum.
@@ -64,7 +64,7 @@ template <bool BF16, bool ALIGNED>
 __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
   constexpr int E = Elems<BF16>::per_vec;
   const int lane = threadIdx.x & 63;
-  const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
   if (task >= a.R_L * a.C) return;
   const int64_t row = task / a.C;
   const int32_t c = (int32_t)(task - row * a.C);
@@ -102,21 +102,28 @@ __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
 // Algorithm 2, "Verification Process" loop: accept x_i iff r_i < min(1, p_i(x_i)/q_i(x_i)),
 // evaluated as r_i*q < p; stop at the first failure.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ float2 merge_row(const BatchView& a, int64_t row) {
-  const float2* cs = a.chunk_stats + row * a.C;
-  float M2 = neg_inf();
-  for (int32_t c = 0; c < a.C; ++c) M2 = fmaxf(M2, cs[c].x);
-  float Z = 0.f;
-  if (M2 > neg_inf())
-    for (int32_t c = 0; c < a.C; ++c) Z += cs[c].y * fast_exp2(cs[c].x - M2);
+// Row (M2, Z) from its chunk pairs, computed by one wave: lane = chunk (batches of 64), fixed
+// butterfly order.  `first` holds the pair of chunk `lane` (already loaded by the caller).
+__device__ __forceinline__ float2 merge_row_wave(const float2* cs, int32_t C, int lane, float2 first) {
+  float M2 = wave_max(lane < C ? first.x : neg_inf());
+  for (int32_t base = kWave; base < C; base += kWave)
+    M2 = fmaxf(M2, wave_max(base + lane < C ? cs[base + lane].x : neg_inf()));
+  if (!(M2 > neg_inf())) return make_float2(M2, 0.f);
+  float Z = wave_sum(lane < C ? first.y * fast_exp2(first.x - M2) : 0.f);
+  for (int32_t base = kWave; base < C; base += kWave) {
+    const int32_t c = base + lane;
+    Z += wave_sum(c < C ? cs[c].y * fast_exp2(cs[c].x - M2) : 0.f);
+  }
   return make_float2(M2, Z);
 }
 
+// One 256-thread workgroup per session.  The four waves merge the session's rows (four rows
+// per wave in flight at a time); wave 0 then takes lane i = draft position i.
 template <bool BF16>
 __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
-  const int lane = threadIdx.x & 63;
-  const int32_t b = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (b >= a.B) return;
+  __shared__ float2 row_st[kWave + 1];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int32_t b = blockIdx.x;
   const int64_t off0 = session_first_draft(a, b);
   const int64_t off1 = a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma;
   int32_t bad = 0;
@@ -132,44 +139,70 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
   int32_t first_reject = g;
   if (!(bad & 4)) {
     for (int32_t base = 0; base <= g; base += kWave) {
-      const int32_t i = base + lane;
-      bool reject = false;
-      int32_t lane_bad = 0;
-      if (i <= g) {
-        const int64_t lrow = lrow0 + i;
-        const float2 st = merge_row(a, lrow);
-        a.row_tab[lrow] = st;
-        if (a.row_stats) {
-          a.row_stats[2 * lrow] = st.x * (kLn2);
-          a.row_stats[2 * lrow + 1] = st.y;
+      // rows base .. base+nrows-1 of the session (the last pass includes the bonus row)
+      const int32_t nrows = min(kWave, g + 1 - base);
+      for (int32_t r0 = wave; r0 < nrows; r0 += 16) {
+        float2 first[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int32_t r = r0 + 4 * j;
+          first[j] = (r < nrows && lane < a.C) ? a.chunk_stats[(lrow0 + base + r) * a.C + lane]
+                                               : make_float2(neg_inf(), 0.f);
         }
-        if (!(st.y > 0.f) || !(st.y < 3.0e38f) || !(fabsf(st.x) < 3.0e38f)) lane_bad |= 8;
-        if (i < g) {
-          const int64_t qrow = off0 + i;
-          const int32_t x = a.tokens[qrow];
-          float p = 0.f, q = 0.f;
-          if (x < 0 || x >= a.V) {
-            lane_bad |= 1;
-          } else {
-            const float zx = load_logit(logits_row<BF16>(a, lrow), x, BF16);
-            p = fast_exp2(fmaf(zx, c1, -st.x)) / st.y;
-            q = a.draft_probs[qrow * (int64_t)a.V + x];
-            const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)i, a.step_lo, a.step_hi, a.seed_lo,
-                             a.seed_hi);
-            const float r = u01(rnd.w[0]);
-            reject = !(__fmul_rn(r, q) < p);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int32_t r = r0 + 4 * j;
+          if (r < nrows) {
+            const int64_t lrow = lrow0 + base + r;
+            const float2 st = merge_row_wave(a.chunk_stats + lrow * a.C, a.C, lane, first[j]);
+            if (lane == 0) {
+              row_st[r] = st;
+              a.row_tab[lrow] = st;
+              if (a.row_stats) {
+                a.row_stats[2 * lrow] = st.x * kLn2;
+                a.row_stats[2 * lrow + 1] = st.y;
+              }
+            }
           }
-          if (a.p_tok) a.p_tok[qrow] = p;
-          if (a.q_tok) a.q_tok[qrow] = q;
         }
       }
-      const uint64_t rej_mask = __ballot(reject);
-      if (rej_mask && first_reject == g) first_reject = base + (__ffsll((long long)rej_mask) - 1);
-      const uint64_t b1 = __ballot(lane_bad & 1), b8 = __ballot(lane_bad & 8);
-      bad |= (b1 ? 1 : 0) | (b8 ? 8 : 0);
+      __syncthreads();
+      if (wave == 0) {
+        const int32_t i = base + lane;
+        bool reject = false;
+        int32_t lane_bad = 0;
+        if (lane < nrows) {
+          const float2 st = row_st[lane];
+          const int64_t lrow = lrow0 + i;
+          if (!(st.y > 0.f) || !(st.y < 3.0e38f) || !(fabsf(st.x) < 3.0e38f)) lane_bad |= 8;
+          if (i < g) {
+            const int64_t qrow = off0 + i;
+            const int32_t x = a.tokens[qrow];
+            float p = 0.f, q = 0.f;
+            if (x < 0 || x >= a.V) {
+              lane_bad |= 1;
+            } else {
+              const float zx = load_logit(logits_row<BF16>(a, lrow), x, BF16);
+              p = fast_exp2(fmaf(zx, c1, -st.x)) / st.y;
+              q = a.draft_probs[qrow * (int64_t)a.V + x];
+              const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)i, a.step_lo, a.step_hi, a.seed_lo,
+                               a.seed_hi);
+              const float r = u01(rnd.w[0]);
+              reject = !(__fmul_rn(r, q) < p);
+            }
+            if (a.p_tok) a.p_tok[qrow] = p;
+            if (a.q_tok) a.q_tok[qrow] = q;
+          }
+        }
+        const uint64_t rej_mask = __ballot(reject);
+        if (rej_mask && first_reject == g) first_reject = base + (__ffsll((long long)rej_mask) - 1);
+        const uint64_t b1 = __ballot(lane_bad & 1), b8 = __ballot(lane_bad & 8);
+        bad |= (b1 ? 1 : 0) | (b8 ? 8 : 0);
+      }
+      __syncthreads();
     }
   }
-  if (lane == 0) {
+  if (threadIdx.x == 0) {
     if (bad) {
       a.accepted_len[b] = 0;
       a.rejected[b] = 1;
@@ -219,8 +252,9 @@ template <bool BF16, bool ALIGNED>
 __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t groups) {
   constexpr int E = Elems<BF16>::per_vec;
   const int lane = threadIdx.x & 63;
-  const int32_t b = blockIdx.x / groups;
-  const int32_t c = (blockIdx.x - b * groups) * 4 + (threadIdx.x >> 6);
+  const int64_t blk = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int32_t b = (int32_t)(blk / groups);
+  const int32_t c = (int32_t)(blk - (int64_t)b * groups) * 4 + (threadIdx.x >> 6);
   if (c >= a.C || a.skip[b] || !a.rejected[b]) return;
   const int64_t off0 = session_first_draft(a, b);
   const int32_t g = a.offsets ? a.offsets[b + 1] - a.offsets[b] : a.gamma;
