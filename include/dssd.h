@@ -16,8 +16,9 @@
  *   - All three hot calls are asynchronous on `hip_stream` (a hipStream_t, NULL = default
  *     stream); they never synchronise, never allocate and never touch host copies of the data.
  *   - dssd_residual_sample and dssd_bonus_sample must follow dssd_verify_batch for the same
- *     batch on the same context and stream: they read accepted_len / rejected and the softmax
- *     statistics that verify left in the context's workspace.
+ *     batch on the same context and stream: they act on the per-session record (row to draw
+ *     from, its softmax statistics) that verify left in the context's workspace, not on the
+ *     caller's copies of accepted_len / rejected.
  *   - One context serves one stream at a time (its workspace is shared by consecutive calls).
  *   - Positions are 0-based: accepted_len = j - 1 in the paper's numbering.
  *   - Host-checkable errors return a negative status before anything is launched.  Errors that

@@ -20,7 +20,8 @@ struct dssd_ctx {
   float2* chunk_stats = nullptr;
   float2* row_tab = nullptr;
   float* resid_mass = nullptr;
-  int32_t* skip = nullptr;
+  Job* resid_job = nullptr;
+  Job* bonus_job = nullptr;
   bool profiling = false;
   std::vector<hipEvent_t> ev_begin[DSSD_K_COUNT], ev_end[DSSD_K_COUNT];
   size_t ev_used[DSSD_K_COUNT] = {0, 0, 0, 0, 0};
@@ -37,7 +38,7 @@ extern "C" size_t dssd_workspace_bytes(int64_t max_rows, int32_t max_V, int32_t 
   const size_t C = (size_t)chunks_per_row(max_V, logits_dtype);
   const size_t rows = (size_t)max_rows;
   return align256(rows * C * sizeof(float2)) + align256(rows * sizeof(float2)) +
-         align256(rows * C * sizeof(float)) + align256(rows * sizeof(int32_t));
+         align256(rows * C * sizeof(float)) + 2 * align256(rows * sizeof(Job));
 }
 
 extern "C" const char* dssd_status_str(dssd_status s) {
@@ -81,7 +82,8 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   c->chunk_stats = reinterpret_cast<float2*>(p); p += align256(rows * C * sizeof(float2));
   c->row_tab = reinterpret_cast<float2*>(p);     p += align256(rows * sizeof(float2));
   c->resid_mass = reinterpret_cast<float*>(p);   p += align256(rows * C * sizeof(float));
-  c->skip = reinterpret_cast<int32_t*>(p);
+  c->resid_job = reinterpret_cast<Job*>(p);      p += align256(rows * sizeof(Job));
+  c->bonus_job = reinterpret_cast<Job*>(p);
   *out = c;
   return DSSD_OK;
 }
@@ -124,7 +126,8 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   v->session_base = b->session_base;
   v->accepted_len = o->accepted_len; v->rejected = o->rejected; v->out_token = o->out_token;
   v->row_stats = o->row_stats; v->p_tok = o->p_tok; v->q_tok = o->q_tok; v->status = o->status;
-  v->chunk_stats = c->chunk_stats; v->row_tab = c->row_tab; v->resid_mass = c->resid_mass; v->skip = c->skip;
+  v->chunk_stats = c->chunk_stats; v->row_tab = c->row_tab; v->resid_mass = c->resid_mass;
+  v->resid_job = c->resid_job; v->bonus_job = c->bonus_job;
   return DSSD_OK;
 }
 

@@ -15,6 +15,13 @@
 
 namespace dssd {
 
+// What verify leaves for the samplers, per session: the logits row to draw from and its
+// softmax statistics.  lrow < 0: nothing to do (other branch taken, or a device-side error).
+struct __attribute__((aligned(16))) Job {
+  int64_t lrow;
+  float M2, Z;
+};
+
 struct BatchView {
   int32_t B, V, gamma, C;            // C = chunks per row
   int64_t R_L, R_Q;
@@ -36,7 +43,8 @@ struct BatchView {
   float2* chunk_stats;               // [R_L, C]  (m2_c, s_c)
   float2* row_tab;                   // [R_L]     (M2, Z) in the log2 domain
   float* resid_mass;                 // [B, C]
-  int32_t* skip;                     // [B] 1 = session had a device-side error
+  Job* resid_job;                    // [B] rejected sessions: row n
+  Job* bonus_job;                    // [B] all-accepted sessions: row gamma_b
 };
 
 __device__ __forceinline__ int64_t session_first_draft(const BatchView& a, int32_t b) {
@@ -137,6 +145,7 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
   const int64_t lrow0 = off0 + b;
   const float c1 = tau * kLog2e;
   int32_t first_reject = g;
+  float2 sel_st = make_float2(0.f, 0.f);   // statistics of the row the session will draw from
   if (!(bad & 4)) {
     for (int32_t base = 0; base <= g; base += kWave) {
       // rows base .. base+nrows-1 of the session (the last pass includes the bonus row)
@@ -195,7 +204,13 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
           }
         }
         const uint64_t rej_mask = __ballot(reject);
-        if (rej_mask && first_reject == g) first_reject = base + (__ffsll((long long)rej_mask) - 1);
+        if (rej_mask && first_reject == g) {
+          const int idx = __ffsll((long long)rej_mask) - 1;
+          first_reject = base + idx;
+          sel_st = row_st[idx];
+        } else if (first_reject == g && base + nrows - 1 == g) {
+          sel_st = row_st[nrows - 1];        // all accepted: the bonus row
+        }
         const uint64_t b1 = __ballot(lane_bad & 1), b8 = __ballot(lane_bad & 8);
         bad |= (b1 ? 1 : 0) | (b8 ? 8 : 0);
       }
@@ -211,7 +226,11 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
       a.accepted_len[b] = first_reject;
       a.rejected[b] = first_reject < g ? 1 : 0;
     }
-    a.skip[b] = bad ? 1 : 0;
+    Job none, job;
+    none.lrow = -1; none.M2 = 0.f; none.Z = 0.f;
+    job.lrow = lrow0 + first_reject; job.M2 = sel_st.x; job.Z = sel_st.y;
+    a.resid_job[b] = (!bad && first_reject < g) ? job : none;
+    a.bonus_job[b] = (!bad && first_reject == g) ? job : none;
     if (a.status) a.status[b] = bad;
   }
 }
@@ -252,26 +271,35 @@ template <bool BF16, bool ALIGNED>
 __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t groups) {
   constexpr int E = Elems<BF16>::per_vec;
   const int lane = threadIdx.x & 63;
-  const int64_t blk = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int64_t blk = blockIdx.x;   // plain order: measured faster here than the XCD-contiguous map
   const int32_t b = (int32_t)(blk / groups);
   const int32_t c = (int32_t)(blk - (int64_t)b * groups) * 4 + (threadIdx.x >> 6);
-  if (c >= a.C || a.skip[b] || !a.rejected[b]) return;
-  const int64_t off0 = session_first_draft(a, b);
-  const int32_t g = a.offsets ? a.offsets[b + 1] - a.offsets[b] : a.gamma;
-  const int32_t n = a.accepted_len[b];
-  if (n < 0 || n >= g) return;   // not the record verify wrote for this batch: touch nothing
-  const int64_t lrow = off0 + b + n;
-  const float2 st = a.row_tab[lrow];
+  if (c >= a.C) return;
+  const Job job = a.resid_job[b];
+  if (job.lrow < 0) return;
+  const int64_t lrow = job.lrow;
+  const float2 st = make_float2(job.M2, job.Z);
   const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
   const float invZ = 1.f / st.y;
   const char* lp = logits_row<BF16>(a, lrow);
-  const float* qp = a.draft_probs + (off0 + n) * (int64_t)a.V;
+  const float* qp = a.draft_probs + (lrow - b) * (int64_t)a.V;   // draft row = logits row - session
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
+  // Two half-chunks of 4 groups each (12 loads in flight per lane): measured faster than all 8
+  // groups at once, which costs occupancy (three input streams here, not one).
   float acc = 0.f;
 #pragma unroll
-  for (int k = 0; k < kUnroll; ++k) {
-    float w[E];
-    acc += group_weights<BF16, ALIGNED, true>(lp, qp, v0 + k * kWave, a.V, c1, st.x, invZ, w);
+  for (int k0 = 0; k0 < kUnroll; k0 += 4) {
+    float z[4][E], q[4][E];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
+      load_probs<E, ALIGNED>(qp, (v0 + (k0 + k) * kWave) * E, a.V, q[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z[k][e], c1, -st.x)), invZ, -q[k][e]));
   }
   acc = wave_sum(acc);
   if (lane == 0) a.resid_mass[(int64_t)b * a.C + c] = acc;
@@ -378,19 +406,16 @@ template <bool BF16, bool ALIGNED, bool RESID>
 __global__ __launch_bounds__(256) void pick_token(const BatchView a) {
   const int lane = threadIdx.x & 63;
   const int32_t b = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (b >= a.B || a.skip[b]) return;
-  const bool rejected = a.rejected[b] != 0;
-  if (rejected != RESID) return;
-  const int64_t off0 = session_first_draft(a, b);
-  const int32_t g = a.offsets ? a.offsets[b + 1] - a.offsets[b] : a.gamma;
-  const int32_t n = a.accepted_len[b];
-  if (RESID ? (n < 0 || n >= g) : (n != g)) return;   // not verify's record for this batch
-  const int64_t lrow = off0 + b + n;
-  const float2 st = a.row_tab[lrow];
+  if (b >= a.B) return;
+  const Job job = RESID ? a.resid_job[b] : a.bonus_job[b];
+  if (job.lrow < 0) return;
+  const int64_t lrow = job.lrow;
+  const int32_t n = (int32_t)(lrow - b - session_first_draft(a, b));   // position inside the session
+  const float2 st = make_float2(job.M2, job.Z);
   const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
   const float invZ = 1.f / st.y;
   const char* lp = logits_row<BF16>(a, lrow);
-  const float* qp = RESID ? a.draft_probs + (off0 + n) * (int64_t)a.V : nullptr;
+  const float* qp = RESID ? a.draft_probs + (lrow - b) * (int64_t)a.V : nullptr;
   const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)n, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi);
   const float r = u01(rnd.w[RESID ? 1 : 2]);
 
