@@ -20,6 +20,27 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
+# HBM bytes per launch of row_chunk_stats from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+# what the same counters read for a plain copy of known size; profiles/row_chunk_stats_cfg4_pmc.txt).
+# Valid only for the kernel sources they were taken with: reported as null once those change.
+PMC_TRAFFIC = {
+    "cfg4_B1024_ragged_g1-16_V256000_bf16": {
+        "sources_sha256": "01fb1af6f1f43f5879498ef09c123ecb129323f392c3116235db6db4d3d3fda2",
+        "bytes_per_launch": int((2426307.9 * 2.0 + 4776.8 * 1.0) * 1024),
+    },
+}
+
+
+def kernel_sources_digest():
+    import hashlib
+    d = os.path.join(ROOT, "paper_2507_12000_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        h.update(name.encode())
+        with open(os.path.join(d, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
 
 def algorithmic_bytes(inputs, rejected, C_bonus_fraction):
     """Bytes the method must move in one step: every logits row once; for each rejected
@@ -148,6 +169,8 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     k1_us = kernels["row_chunk_stats"]["avg_us"]
     achieved = ab["row_stats"] / (k1_us * 1e-6) / 1e9
+    pmc = PMC_TRAFFIC.get(w.name)
+    traffic = pmc["bytes_per_launch"] if pmc and pmc["sources_sha256"] == kernel_sources_digest() else None
     result = {
         "metric": "verified_draft_positions_per_sec",
         "value": inputs["R_Q"] * args.steps / elapsed,
@@ -165,7 +188,7 @@ def main():
         "kernels": kernels,
         "roofline": {"bound": "hbm", "kernel": "row_chunk_stats", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes_per_launch": ab["row_stats"],
+                     "traffic": traffic, "algorithmic_bytes_per_launch": ab["row_stats"],
                      "avg_launch_us": k1_us},
     }
     if not args.no_cpu_baseline:
