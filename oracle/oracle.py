@@ -29,7 +29,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # DSSD_ORACLE_LIB lets the tests load a deliberately broken build to prove the pins bite
+        path = os.environ.get("DSSD_ORACLE_LIB") or _build.build(force=False)
         L = C.CDLL(path)
         vp, dp, ip = C.c_void_p, C.c_void_p, C.c_void_p
         L.dssd_oracle_philox4x32_10.argtypes = [vp, vp, vp]
