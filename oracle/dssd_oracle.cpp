@@ -40,6 +40,13 @@
 // on tiny vocabularies; chi-square Monte Carlo on whole sample paths; the paper's
 // Table 1 column 1 - alpha^gamma; invariants.
 //
+// The second half of the file states the same step as the paper's split (Sec. 3): an edge
+// function that sees only tokens and the scalars q_j(x_j) and emits either the bonus token
+// or the b_prob-bit distribution P_j, and a device function that redraws from the received
+// P_j and its own Q_j.  Pins: with an exact downlink the split equals the unsplit step bit
+// for bit; the binary16 rounding agrees with numpy's converter on every half value's
+// neighbourhood; the device draw agrees with a numpy restatement.
+//
 // Build: g++ -O2 -std=c++17 -shared -fPIC (no -ffast-math: summation order is part
 // of the definition).
 
@@ -296,6 +303,170 @@ void dssd_oracle_verify_batch(int32_t B, int32_t V, int32_t gamma, const int32_t
         res + b, p_tok ? p_tok + off : nullptr, q_tok ? q_tok + off : nullptr,
         r_acc ? r_acc + off : nullptr, row_m ? row_m + lrow : nullptr,
         row_Z ? row_Z + lrow : nullptr, beta ? beta + off : nullptr);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The split of Algorithm 2 (Sec. 3): what the edge and the device each compute
+// when only DSSD's payloads cross the link.
+//   uplink   : tokens x_i and the scalars q_i(x_i)            (no Q rows at the edge)
+//   downlink : if Flag = 0, the distribution P_j(x) in b_prob-bit values, and j;
+//              else the bonus token and gamma+1
+//   device   : x'_j ~ norm(max(0, P_j - Q_j)) from the received P_j and its own Q_j
+// b_prob = 32 is IEEE fp32, b_prob = 16 is IEEE fp16 (Sec. 2.2: "32 bits for full
+// precision or 16 bits for half precision"); both are rounded to nearest-even from
+// the fp32 value of P, the precision the GPU library computes P in.  p_dtype 3
+// (fp64, no rounding) exists only to pin the split against the unsplit path.
+// ---------------------------------------------------------------------------
+enum { ORACLE_P_F32 = 0, ORACLE_P_F16 = 2, ORACLE_P_F64 = 3 };
+
+// fp32 -> IEEE binary16, round to nearest, ties to even; subnormals kept.
+uint16_t dssd_oracle_f32_to_f16(float f) {
+  uint32_t bits;
+  std::memcpy(&bits, &f, sizeof bits);
+  const uint32_t sign = (bits >> 16) & 0x8000u;
+  const int32_t exp32 = (int32_t)((bits >> 23) & 0xFFu);
+  uint32_t man = bits & 0x7FFFFFu;
+  if (exp32 == 255) return (uint16_t)(sign | 0x7C00u | (man ? 0x200u : 0u));
+  const int32_t e = exp32 - 127 + 15;
+  if (e >= 31) return (uint16_t)(sign | 0x7C00u);
+  if (e <= 0) {
+    if (e < -10) return (uint16_t)sign;          // below half of the smallest subnormal
+    man |= 0x800000u;                            // implicit one
+    const int shift = 14 - e;                    // 14 .. 24
+    uint32_t half = man >> shift;
+    const uint32_t rem = man & ((1u << shift) - 1u), mid = 1u << (shift - 1);
+    if (rem > mid || (rem == mid && (half & 1u))) ++half;
+    return (uint16_t)(sign | half);
+  }
+  uint32_t half = ((uint32_t)e << 10) | (man >> 13);
+  const uint32_t rem = man & 0x1FFFu;
+  if (rem > 0x1000u || (rem == 0x1000u && (half & 1u))) ++half;   // may carry into the exponent
+  return (uint16_t)(sign | half);
+}
+
+double dssd_oracle_f16_to_f64(uint16_t h) {
+  const int sign = (h >> 15) & 1, e = (h >> 10) & 0x1F, man = h & 0x3FF;
+  double v;
+  if (e == 0) v = std::ldexp((double)man, -24);
+  else if (e == 31) v = man ? std::numeric_limits<double>::quiet_NaN() : std::numeric_limits<double>::infinity();
+  else v = std::ldexp((double)(man | 0x400), e - 25);
+  return sign ? -v : v;
+}
+
+static size_t p_elem_size(int p_dtype) { return p_dtype == ORACLE_P_F16 ? 2 : p_dtype == ORACLE_P_F32 ? 4 : 8; }
+
+// The downlink payload: P in b_prob-bit values.
+void dssd_oracle_quantize_p_row(const double* P, int32_t V, int p_dtype, void* out) {
+  for (int32_t v = 0; v < V; ++v) {
+    if (p_dtype == ORACLE_P_F64) ((double*)out)[v] = P[v];
+    else if (p_dtype == ORACLE_P_F32) ((float*)out)[v] = (float)P[v];
+    else ((uint16_t*)out)[v] = dssd_oracle_f32_to_f16((float)P[v]);
+  }
+}
+
+static double p_at(const void* row, int p_dtype, int32_t v) {
+  if (p_dtype == ORACLE_P_F64) return ((const double*)row)[v];
+  if (p_dtype == ORACLE_P_F32) return (double)((const float*)row)[v];
+  return dssd_oracle_f16_to_f64(((const uint16_t*)row)[v]);
+}
+
+// Edge side of one session.  q_scalars[i] = q_i(x_i) as uploaded.  On a rejection the
+// P row of the rejected position is written to p_row_out in p_dtype; otherwise the bonus
+// token is drawn.  res->token is -1 for rejected sessions: the edge does not redraw.
+void dssd_oracle_edge_session(const void* logits, int dtype, const float* q_scalars,
+                              const int32_t* tokens, int32_t gamma, int32_t V, double inv_temperature,
+                              uint64_t seed, uint64_t step, uint32_t session, int p_dtype,
+                              dssd_oracle_result* res, void* p_row_out, double* p_tok) {
+  const size_t elem = dtype == 0 ? 4 : 2;
+  std::vector<double> P((size_t)V);
+  res->n = gamma; res->rejected = 0; res->token = -1; res->status = 0;
+  res->resid_mass = 0.0; res->cdf_margin = 0.0;
+  res->accept_margin = std::numeric_limits<double>::infinity();
+  for (int32_t i = 0; i < gamma; ++i)
+    if (tokens[i] < 0 || tokens[i] >= V) res->status |= 1;
+  if (res->status & 1) { res->n = 0; res->rejected = 1; return; }
+  for (int32_t i = 0; i <= gamma; ++i) {
+    double m, Z;
+    dssd_oracle_softmax_row((const char*)logits + (size_t)i * (size_t)V * elem, dtype, V,
+                            inv_temperature, P.data(), &m, &Z);
+    uint32_t words[4];
+    dssd_oracle_random_block(seed, step, session, (uint32_t)i, words);
+    if (i == gamma) {   // all accepted: bonus token, word 2 of the position-gamma block
+      res->token = dssd_oracle_inverse_cdf(P.data(), V, dssd_oracle_u01(words[2]), &res->cdf_margin);
+      return;
+    }
+    const double p = P[tokens[i]], q = (double)q_scalars[i], r = dssd_oracle_u01(words[0]);
+    if (p_tok) p_tok[i] = p;
+    const double gap = std::fabs(r * q - p);
+    const double margin = q > 0.0 ? gap / q : (p > 1e-30 ? std::numeric_limits<double>::infinity() : 0.0);
+    if (margin < res->accept_margin) res->accept_margin = margin;
+    if (!dssd_oracle_accept(r, p, q)) {
+      res->n = i;
+      res->rejected = 1;
+      dssd_oracle_quantize_p_row(P.data(), V, p_dtype, p_row_out);
+      return;
+    }
+  }
+}
+
+// Device side of one session: it knows j (n = j - 1), received P_j, and owns Q_j.
+// Draws with word 1 of the position-n block.  Returns the token; fills R, the margin and
+// status bit 1 (zero residual: drew from the received P_j).
+int32_t dssd_oracle_device_session(const void* p_row, int p_dtype, const float* Q_row, int32_t V,
+                                   int32_t n, uint64_t seed, uint64_t step, uint32_t session,
+                                   double* resid_mass, double* cdf_margin, int32_t* status) {
+  std::vector<double> P((size_t)V), w((size_t)V);
+  for (int32_t v = 0; v < V; ++v) P[v] = p_at(p_row, p_dtype, v);
+  const double R = dssd_oracle_residual(P.data(), Q_row, V, w.data());
+  uint32_t words[4];
+  dssd_oracle_random_block(seed, step, session, (uint32_t)n, words);
+  const double r = dssd_oracle_u01(words[1]);
+  if (resid_mass) *resid_mass = R;
+  if (status) *status = 0;
+  if (R > 0.0) return dssd_oracle_inverse_cdf(w.data(), V, r, cdf_margin);
+  if (status) *status = 2;
+  return dssd_oracle_inverse_cdf(P.data(), V, r, cdf_margin);
+}
+
+// Batch forms.  p_rows is [B, V] in p_dtype, row b written (edge) / read (device) only for
+// rejected sessions.  Layout of everything else as in dssd_oracle_verify_batch.
+void dssd_oracle_edge_batch(int32_t B, int32_t V, int32_t gamma, const int32_t* draft_offsets,
+                            const void* logits, int dtype, const float* q_scalars,
+                            const int32_t* draft_tokens, const float* inv_temperature, uint64_t seed,
+                            uint64_t step, uint32_t session_base, int p_dtype,
+                            dssd_oracle_result* res, void* p_rows, double* p_tok) {
+  const size_t elem = dtype == 0 ? 4 : 2;
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t off = draft_offsets ? draft_offsets[b] : (int64_t)b * gamma;
+    const int32_t g = draft_offsets ? draft_offsets[b + 1] - draft_offsets[b] : gamma;
+    dssd_oracle_edge_session((const char*)logits + (size_t)(off + b) * (size_t)V * elem, dtype,
+                             q_scalars + off, draft_tokens + off, g, V,
+                             inv_temperature ? (double)inv_temperature[b] : 1.0, seed, step,
+                             session_base + (uint32_t)b, p_dtype, res + b,
+                             (char*)p_rows + (size_t)b * (size_t)V * p_elem_size(p_dtype),
+                             p_tok ? p_tok + off : nullptr);
+  }
+}
+
+void dssd_oracle_device_batch(int32_t B, int32_t V, int32_t gamma, const int32_t* draft_offsets,
+                              const float* draft_probs, const void* p_rows, int p_dtype,
+                              const int32_t* accepted_len, const int32_t* rejected, uint64_t seed,
+                              uint64_t step, uint32_t session_base, int32_t* token,
+                              double* resid_mass, double* cdf_margin, int32_t* status) {
+  for (int32_t b = 0; b < B; ++b) {
+    token[b] = -1;
+    if (status) status[b] = 0;
+    if (!rejected[b]) continue;
+    const int64_t off = draft_offsets ? draft_offsets[b] : (int64_t)b * gamma;
+    const int32_t g = draft_offsets ? draft_offsets[b + 1] - draft_offsets[b] : gamma;
+    const int32_t n = accepted_len[b];
+    if (n < 0 || n >= g) { if (status) status[b] = 4; continue; }
+    token[b] = dssd_oracle_device_session(
+        (const char*)p_rows + (size_t)b * (size_t)V * p_elem_size(p_dtype), p_dtype,
+        draft_probs + (size_t)(off + n) * (size_t)V, V, n, seed, step, session_base + (uint32_t)b,
+        resid_mass ? resid_mass + b : nullptr, cdf_margin ? cdf_margin + b : nullptr,
+        status ? status + b : nullptr);
   }
 }
 

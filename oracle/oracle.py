@@ -169,3 +169,89 @@ def verify_batch(logits, dtype, draft_probs, draft_tokens, V, gamma=0, draft_off
                                    _ptr(p_tok), _ptr(q_tok), _ptr(r_acc), _ptr(row_m), _ptr(row_Z),
                                    _ptr(beta))
     return dict(res=res, p_tok=p_tok, q_tok=q_tok, r_acc=r_acc, row_m=row_m, row_Z=row_Z, beta=beta)
+
+
+# ------------------------------------------------------------------ the edge / device split
+P_F32, P_F16, P_F64 = 0, 2, 3
+_P_NP = {P_F32: np.float32, P_F16: np.uint16, P_F64: np.float64}
+
+
+def _split_lib():
+    L = lib()
+    if not getattr(L, "_split_ready", False):
+        vp = C.c_void_p
+        L.dssd_oracle_f32_to_f16.argtypes = [C.c_float]
+        L.dssd_oracle_f32_to_f16.restype = C.c_uint16
+        L.dssd_oracle_f16_to_f64.argtypes = [C.c_uint16]
+        L.dssd_oracle_f16_to_f64.restype = C.c_double
+        L.dssd_oracle_quantize_p_row.argtypes = [vp, C.c_int32, C.c_int, vp]
+        L.dssd_oracle_quantize_p_row.restype = None
+        L.dssd_oracle_edge_batch.argtypes = [C.c_int32, C.c_int32, C.c_int32, vp, vp, C.c_int, vp, vp, vp,
+                                             C.c_uint64, C.c_uint64, C.c_uint32, C.c_int, vp, vp, vp]
+        L.dssd_oracle_edge_batch.restype = None
+        L.dssd_oracle_device_batch.argtypes = [C.c_int32, C.c_int32, C.c_int32, vp, vp, vp, C.c_int, vp, vp,
+                                               C.c_uint64, C.c_uint64, C.c_uint32, vp, vp, vp, vp]
+        L.dssd_oracle_device_batch.restype = None
+        L._split_ready = True
+    return L
+
+
+def f32_to_f16(x):
+    return _split_lib().dssd_oracle_f32_to_f16(float(x))
+
+
+def f16_to_f64(h):
+    return _split_lib().dssd_oracle_f16_to_f64(int(h))
+
+
+def quantize_p_row(P, p_dtype):
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    out = np.zeros(P.shape[0], dtype=_P_NP[p_dtype])
+    _split_lib().dssd_oracle_quantize_p_row(_ptr(P), P.shape[0], p_dtype, _ptr(out))
+    return out
+
+
+def _layout(draft_offsets, draft_tokens, gamma):
+    if draft_offsets is not None:
+        off = np.ascontiguousarray(draft_offsets, dtype=np.int32)
+        return off, off.shape[0] - 1, int(off[-1])
+    R_Q = int(np.asarray(draft_tokens).size)
+    return None, (R_Q // gamma if gamma > 0 else None), R_Q
+
+
+def edge_batch(logits, dtype, q_scalars, draft_tokens, V, p_dtype, gamma=0, draft_offsets=None,
+               inv_temperature=None, seed=0, step=0, session_base=0, B=None):
+    """Edge side of the split.  Returns dict: 'res' (token = bonus token or -1), 'p_rows' [B, V]
+    in p_dtype (rows of rejected sessions only are meaningful), 'p_tok'."""
+    lg = _logits_array(logits, dtype)
+    off, B2, R_Q = _layout(draft_offsets, draft_tokens, gamma)
+    B = B2 if B2 is not None else (B if B is not None else lg.size // V)
+    qs = np.ascontiguousarray(q_scalars, dtype=np.float32)
+    tk = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    it = None if inv_temperature is None else np.ascontiguousarray(inv_temperature, dtype=np.float32)
+    res = np.zeros(B, dtype=RESULT_DTYPE)
+    p_rows = np.zeros((B, V), dtype=_P_NP[p_dtype])
+    p_tok = np.full(R_Q, np.nan)
+    _split_lib().dssd_oracle_edge_batch(B, V, gamma, _ptr(off), _ptr(lg), dtype, _ptr(qs), _ptr(tk), _ptr(it),
+                                        int(seed), int(step), int(session_base), p_dtype, _ptr(res),
+                                        _ptr(p_rows), _ptr(p_tok))
+    return dict(res=res, p_rows=p_rows, p_tok=p_tok)
+
+
+def device_batch(draft_probs, p_rows, p_dtype, accepted_len, rejected, V, gamma=0, draft_offsets=None,
+                 seed=0, step=0, session_base=0):
+    """Device side of the split.  Returns dict: 'token' (-1 where not rejected), 'resid_mass',
+    'cdf_margin', 'status'."""
+    off = None if draft_offsets is None else np.ascontiguousarray(draft_offsets, dtype=np.int32)
+    al = np.ascontiguousarray(accepted_len, dtype=np.int32)
+    rj = np.ascontiguousarray(rejected, dtype=np.int32)
+    B = al.shape[0]
+    dq = np.ascontiguousarray(draft_probs, dtype=np.float32)
+    pr = np.ascontiguousarray(p_rows, dtype=_P_NP[p_dtype])
+    assert pr.size == B * V
+    token = np.zeros(B, dtype=np.int32)
+    R = np.zeros(B); margin = np.zeros(B); status = np.zeros(B, dtype=np.int32)
+    _split_lib().dssd_oracle_device_batch(B, V, gamma, _ptr(off), _ptr(dq), _ptr(pr), p_dtype, _ptr(al), _ptr(rj),
+                                          int(seed), int(step), int(session_base), _ptr(token), _ptr(R),
+                                          _ptr(margin), _ptr(status))
+    return dict(token=token, resid_mass=R, cdf_margin=margin, status=status)
