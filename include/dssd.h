@@ -38,7 +38,7 @@ extern "C" {
 
 typedef struct dssd_ctx dssd_ctx; /* opaque: device workspace + profiling events */
 
-typedef enum { DSSD_F32 = 0, DSSD_BF16 = 1 } dssd_dtype;
+typedef enum { DSSD_F32 = 0, DSSD_BF16 = 1, DSSD_F16 = 2 /* IEEE binary16: downlink P rows only */ } dssd_dtype;
 
 typedef enum {
   DSSD_OK = 0,
@@ -75,7 +75,9 @@ typedef struct {
   const int32_t *draft_offsets; /* [B+1] prefix sums of gamma_b, or NULL for uniform gamma         */
   const void *logits;           /* [R_L, V] row-major contiguous target logits, fp32 or bf16       */
   const float *draft_probs;     /* [R_Q, V] row-major fp32 draft distributions Q_i, each row
-                                   already a probability vector; used as given                     */
+                                   already a probability vector; used as given.  May be NULL for
+                                   dssd_verify_batch / dssd_bonus_sample / dssd_export_p_rows when
+                                   draft_q_tok is given (the edge of DSSD never sees Q rows)       */
   const int32_t *draft_tokens;  /* [R_Q] draft token ids x_i in [0, V)                             */
   const float *inv_temperature; /* [B] 1/T_b > 0 multiplying the target logits before the softmax,
                                    or NULL for T = 1 (the paper's setting)                         */
@@ -86,6 +88,9 @@ typedef struct {
                                    position, word 2 the bonus draw (position gamma_b)              */
   uint32_t session_base;        /* global id of session 0 (keeps results independent of sharding)  */
   uint32_t reserved;
+  const float *draft_q_tok;     /* [R_Q] or NULL: the scalars q_i(x_i) that DSSD uploads with the
+                                   tokens (Sec. 3 "Uplink Transmission"); read only when
+                                   draft_probs is NULL                                             */
 } dssd_batch;
 
 /* Output of one step: the paper's (x_j, j) record per session plus what the samplers and the
@@ -130,13 +135,48 @@ dssd_status dssd_residual_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_ou
  * position-gamma_b block.  Other sessions are untouched. */
 dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
 
+/* Edge side, Algorithm 2 "Downlink Transmission": after dssd_verify_batch, for every session
+ * with rejected = 1 write the distribution at the rejected position, P_n(v) for v in [0, V), into
+ * p_rows[b*V + v] as b_prob-bit values: p_dtype = DSSD_F32 (b_prob = 32) or DSSD_F16 (b_prob = 16,
+ * round to nearest even from the fp32 value).  p_rows is a device buffer of B*V values owned by
+ * the caller; rows of sessions that were not rejected are left untouched. */
+dssd_status dssd_export_p_rows(dssd_ctx *ctx, const dssd_batch *batch, void *p_rows, int32_t p_dtype,
+                               void *hip_stream);
+
+/* What the device of DSSD holds when it redraws (Sec. 3 "Verification Process (on Device)"): its
+ * own Q rows, the received j (accepted_len = j - 1, rejected) and the received P_j rows.  All
+ * pointers are device pointers owned by the caller; layout of sessions as in dssd_batch. */
+typedef struct {
+  int32_t B, V, gamma;          /* as in dssd_batch                                                 */
+  int32_t p_dtype;              /* DSSD_F32 or DSSD_F16: type of p_rows                             */
+  int64_t total_drafts;         /* R_Q                                                              */
+  const int32_t *draft_offsets; /* [B+1] or NULL                                                    */
+  const float *draft_probs;     /* [R_Q, V] fp32 Q rows                                             */
+  const void *p_rows;           /* [B, V] received P_n of session b (read for rejected sessions)    */
+  const int32_t *accepted_len;  /* [B] received n_b                                                 */
+  const int32_t *rejected;      /* [B] received flag                                                */
+  uint64_t seed, step;          /* same Philox key / step as the edge used                          */
+  uint32_t session_base, reserved;
+  int32_t *out_token;           /* [B] written for rejected sessions only                           */
+  int32_t *status;              /* [B] or NULL: DSSD_SESSION_* bits (written for rejected sessions) */
+} dssd_device_batch;
+
+/* Device side, Algorithm 2 "Resample" from what crossed the link: for every rejected session,
+ * out_token = x ~ norm(max(0, P~_n - Q_n)) with P~_n the received row, same inverse-CDF rule and
+ * the same random word (word 1 of the position-n block) as dssd_residual_sample.  Needs a context
+ * (for its workspace) but no preceding verify call on it.  A record with n_b outside [0, gamma_b)
+ * sets DSSD_SESSION_BAD_OFFSETS and out_token = -1. */
+dssd_status dssd_residual_sample_from_p(dssd_ctx *ctx, const dssd_device_batch *batch, void *hip_stream);
+
 const char *dssd_status_str(dssd_status s);
 
 /* Kernel timing (measurement aid, not on the hot path).  While enabled, every kernel launch is
  * bracketed by HIP events on the launch stream.  Kernel ids: 0 row softmax statistics,
- * 1 accept / first-reject, 2 residual chunk masses, 3 residual pick, 4 bonus pick. */
+ * 1 accept / first-reject, 2 residual chunk masses, 3 residual pick, 4 bonus pick, 5 export of
+ * P rows, 6 and 7 chunk masses and pick of the device-side redraw. */
 enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
-       DSSD_K_BONUS_PICK = 4, DSSD_K_COUNT = 5 };
+       DSSD_K_BONUS_PICK = 4, DSSD_K_EXPORT_P = 5, DSSD_K_DEVICE_MASS = 6, DSSD_K_DEVICE_PICK = 7,
+       DSSD_K_COUNT = 8 };
 dssd_status dssd_profile_enable(dssd_ctx *ctx, int enable);
 /* Synchronises the recorded events, returns the summed duration (ms) and number of launches
  * of one kernel since the last reset. */

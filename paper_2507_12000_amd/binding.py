@@ -9,14 +9,16 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdssd.so")
 
-DSSD_F32, DSSD_BF16 = 0, 1
+DSSD_F32, DSSD_BF16, DSSD_F16 = 0, 1, 2
 DSSD_OK, DSSD_EINVAL, DSSD_EALIGN, DSSD_ENOMEM, DSSD_EHIP, DSSD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 SESSION_BAD_TOKEN, SESSION_ZERO_RESIDUAL, SESSION_BAD_OFFSETS, SESSION_BAD_ROW = 1, 2, 4, 8
-K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK, K_COUNT = 0, 1, 2, 3, 4, 5
+K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
+K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_COUNT = 5, 6, 7, 8
 
 # every symbol include/dssd.h declares
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
-           "dssd_residual_sample", "dssd_bonus_sample", "dssd_status_str", "dssd_profile_enable",
+           "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
+           "dssd_residual_sample_from_p", "dssd_status_str", "dssd_profile_enable",
            "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name")
 
 
@@ -25,7 +27,15 @@ class dssd_batch(C.Structure):
                 ("total_drafts", C.c_int64), ("draft_offsets", C.c_void_p), ("logits", C.c_void_p),
                 ("draft_probs", C.c_void_p), ("draft_tokens", C.c_void_p),
                 ("inv_temperature", C.c_void_p), ("seed", C.c_uint64), ("step", C.c_uint64),
-                ("session_base", C.c_uint32), ("reserved", C.c_uint32)]
+                ("session_base", C.c_uint32), ("reserved", C.c_uint32), ("draft_q_tok", C.c_void_p)]
+
+
+class dssd_device_batch(C.Structure):
+    _fields_ = [("B", C.c_int32), ("V", C.c_int32), ("gamma", C.c_int32), ("p_dtype", C.c_int32),
+                ("total_drafts", C.c_int64), ("draft_offsets", C.c_void_p), ("draft_probs", C.c_void_p),
+                ("p_rows", C.c_void_p), ("accepted_len", C.c_void_p), ("rejected", C.c_void_p),
+                ("seed", C.c_uint64), ("step", C.c_uint64), ("session_base", C.c_uint32),
+                ("reserved", C.c_uint32), ("out_token", C.c_void_p), ("status", C.c_void_p)]
 
 
 class dssd_out(C.Structure):
@@ -63,6 +73,10 @@ def load():
         f = getattr(L, name)
         f.argtypes = [P, C.POINTER(dssd_batch), C.POINTER(dssd_out), P]
         f.restype = C.c_int
+    L.dssd_export_p_rows.argtypes = [P, C.POINTER(dssd_batch), P, C.c_int32, P]
+    L.dssd_export_p_rows.restype = C.c_int
+    L.dssd_residual_sample_from_p.argtypes = [P, C.POINTER(dssd_device_batch), P]
+    L.dssd_residual_sample_from_p.restype = C.c_int
     L.dssd_status_str.argtypes = [C.c_int]
     L.dssd_status_str.restype = C.c_char_p
     L.dssd_kernel_name.argtypes = [C.c_int]
@@ -121,6 +135,20 @@ def dssd_bonus_sample(ctx, batch, out, stream=0, check=True):
     return _call("dssd_bonus_sample", ctx, batch, out, stream, check)
 
 
+def dssd_export_p_rows(ctx, batch, p_rows_ptr, p_dtype, stream=0, check=True):
+    rc = load().dssd_export_p_rows(ctx, C.byref(batch), C.c_void_p(p_rows_ptr), int(p_dtype), C.c_void_p(stream or 0))
+    if check and rc != DSSD_OK:
+        raise DssdError(rc, "dssd_export_p_rows")
+    return rc
+
+
+def dssd_residual_sample_from_p(ctx, device_batch, stream=0, check=True):
+    rc = load().dssd_residual_sample_from_p(ctx, C.byref(device_batch), C.c_void_p(stream or 0))
+    if check and rc != DSSD_OK:
+        raise DssdError(rc, "dssd_residual_sample_from_p")
+    return rc
+
+
 def dssd_profile_enable(ctx, enable=True):
     return load().dssd_profile_enable(ctx, 1 if enable else 0)
 
@@ -142,8 +170,24 @@ def _dp(t):
     return None if t is None else t.data_ptr()
 
 
-def make_batch(inputs, seed=0, step=0, session_base=0):
-    """dssd_batch from a dict of device tensors as `synth.generate` returns them."""
+def make_device_batch(inputs, p_rows, accepted_len, rejected, out_token, status=None, seed=0, step=0,
+                      session_base=0):
+    """dssd_device_batch: the device side's view (Q rows, received P rows and j)."""
+    import torch
+    assert p_rows.is_contiguous() and p_rows.dtype in (torch.float32, torch.float16)
+    off = inputs.get("draft_offsets")
+    return dssd_device_batch(B=inputs["B"], V=inputs["V"], gamma=inputs["gamma"],
+                             p_dtype=DSSD_F32 if p_rows.dtype == torch.float32 else DSSD_F16,
+                             total_drafts=inputs["R_Q"], draft_offsets=_dp(off),
+                             draft_probs=_dp(inputs["draft_probs"]), p_rows=_dp(p_rows),
+                             accepted_len=_dp(accepted_len), rejected=_dp(rejected), seed=seed, step=step,
+                             session_base=session_base, reserved=0, out_token=_dp(out_token),
+                             status=_dp(status))
+
+
+def make_batch(inputs, seed=0, step=0, session_base=0, q_scalars=None):
+    """dssd_batch from a dict of device tensors as `synth.generate` returns them.  With
+    `q_scalars` ([R_Q] fp32) the batch carries those instead of the Q rows (the edge's view)."""
     import torch
     lg = inputs["logits"]
     assert lg.is_contiguous() and inputs["draft_probs"].is_contiguous()
@@ -156,8 +200,10 @@ def make_batch(inputs, seed=0, step=0, session_base=0):
     return dssd_batch(B=inputs["B"], V=inputs["V"], gamma=inputs["gamma"],
                       logits_dtype=DSSD_F32 if lg.dtype == torch.float32 else DSSD_BF16,
                       total_drafts=inputs["R_Q"], draft_offsets=_dp(off), logits=_dp(lg),
-                      draft_probs=_dp(inputs["draft_probs"]), draft_tokens=_dp(inputs["draft_tokens"]),
-                      inv_temperature=_dp(it), seed=seed, step=step, session_base=session_base, reserved=0)
+                      draft_probs=None if q_scalars is not None else _dp(inputs["draft_probs"]),
+                      draft_tokens=_dp(inputs["draft_tokens"]),
+                      inv_temperature=_dp(it), seed=seed, step=step, session_base=session_base, reserved=0,
+                      draft_q_tok=_dp(q_scalars))
 
 
 def alloc_out(inputs, device, debug=True):

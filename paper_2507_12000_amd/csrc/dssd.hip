@@ -7,7 +7,7 @@
 #include <new>
 #include <vector>
 
-#include "dssd_kernels.hpp"
+#include "dssd_split_kernels.hpp"
 
 using namespace dssd;
 
@@ -24,7 +24,7 @@ struct dssd_ctx {
   Job* bonus_job = nullptr;
   bool profiling = false;
   std::vector<hipEvent_t> ev_begin[DSSD_K_COUNT], ev_end[DSSD_K_COUNT];
-  size_t ev_used[DSSD_K_COUNT] = {0, 0, 0, 0, 0};
+  size_t ev_used[DSSD_K_COUNT] = {};
 };
 
 static inline int32_t chunks_per_row(int32_t V, int32_t dtype) {
@@ -54,8 +54,9 @@ extern "C" const char* dssd_status_str(dssd_status s) {
 }
 
 extern "C" const char* dssd_kernel_name(int k) {
-  static const char* names[DSSD_K_COUNT] = {"row_chunk_stats", "accept_scan", "resid_mass",
-                                            "resid_pick", "bonus_pick"};
+  static const char* names[DSSD_K_COUNT] = {"row_chunk_stats", "accept_scan", "resid_mass", "resid_pick",
+                                            "bonus_pick", "export_p_rows", "device_resid_mass",
+                                            "device_resid_pick"};
   return (k >= 0 && k < DSSD_K_COUNT) ? names[k] : "?";
 }
 
@@ -99,18 +100,22 @@ extern "C" void dssd_destroy(dssd_ctx* c) {
 }
 
 // Host-side checks shared by the three hot calls.  Fills the kernel argument block.
-static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const dssd_out* o, BatchView* v) {
+static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const dssd_out* o, BatchView* v,
+                                  bool need_out = true) {
+  static const dssd_out no_out = {};
+  if (!need_out && !o) o = &no_out;
   if (!c || !b || !o) return DSSD_EINVAL;
   if (b->B < 0 || b->V < 1 || b->gamma < 0 || b->total_drafts < 0) return DSSD_EINVAL;
   if (b->logits_dtype != DSSD_F32 && b->logits_dtype != DSSD_BF16) return DSSD_EINVAL;
   if (!b->draft_offsets && b->total_drafts != (int64_t)b->B * b->gamma) return DSSD_EINVAL;
   if (b->B > 0) {
-    if (!b->logits || !o->accepted_len || !o->rejected || !o->out_token) return DSSD_EINVAL;
-    if (b->total_drafts > 0 && (!b->draft_probs || !b->draft_tokens)) return DSSD_EINVAL;
+    if (!b->logits) return DSSD_EINVAL;
+    if (need_out && (!o->accepted_len || !o->rejected || !o->out_token)) return DSSD_EINVAL;
+    if (b->total_drafts > 0 && (!b->draft_tokens || (!b->draft_probs && !b->draft_q_tok))) return DSSD_EINVAL;
   }
   const uintptr_t esz = b->logits_dtype == DSSD_BF16 ? 2 : 4;
   auto mis = [](const void* p, uintptr_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) != 0; };
-  if (mis(b->logits, esz) || mis(b->draft_probs, 4) || mis(b->draft_tokens, 4) || mis(b->draft_offsets, 4) ||
+  if (mis(b->logits, esz) || mis(b->draft_probs, 4) || mis(b->draft_q_tok, 4) || mis(b->draft_tokens, 4) || mis(b->draft_offsets, 4) ||
       mis(b->inv_temperature, 4) || mis(o->accepted_len, 4) || mis(o->rejected, 4) || mis(o->out_token, 4) ||
       mis(o->row_stats, 4) || mis(o->p_tok, 4) || mis(o->q_tok, 4) || mis(o->status, 4))
     return DSSD_EALIGN;
@@ -120,6 +125,7 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   v->B = b->B; v->V = b->V; v->gamma = b->gamma; v->C = C;
   v->R_L = R_L; v->R_Q = b->total_drafts;
   v->offsets = b->draft_offsets; v->logits = b->logits; v->draft_probs = b->draft_probs;
+  v->q_scalars = b->draft_probs ? nullptr : b->draft_q_tok;   // Q rows win when both are given
   v->tokens = b->draft_tokens; v->inv_temp = b->inv_temperature;
   v->seed_lo = (uint32_t)b->seed; v->seed_hi = (uint32_t)(b->seed >> 32);
   v->step_lo = (uint32_t)b->step; v->step_hi = (uint32_t)(b->step >> 32);
@@ -135,7 +141,7 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
 static bool vector_ok(const dssd_batch* b) {
   const int per_vec = b->logits_dtype == DSSD_BF16 ? 8 : 4;
   auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-  return (b->V % per_vec) == 0 && al16(b->logits) && al16(b->draft_probs);
+  return (b->V % per_vec) == 0 && al16(b->logits) && al16(b->draft_probs);   // a null pointer counts as aligned
 }
 
 namespace {
@@ -191,6 +197,7 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   const dssd_status st = check_and_view(c, b, o, &v);
   if (st != DSSD_OK || b->B == 0) return st;
   if (b->total_drafts == 0) return DSSD_OK;   // nothing can have been rejected
+  if (!b->draft_probs) return DSSD_EINVAL;    // the residual needs the full Q rows
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
   const int32_t groups = (v.C + 3) / 4;
@@ -221,6 +228,74 @@ extern "C" dssd_status dssd_bonus_sample(dssd_ctx* c, const dssd_batch* b, dssd_
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     if (bf16) { if (al) DSSD_LAUNCH((pick_token<true, true, false>), g2, s, v); else DSSD_LAUNCH((pick_token<true, false, false>), g2, s, v); }
     else      { if (al) DSSD_LAUNCH((pick_token<false, true, false>), g2, s, v); else DSSD_LAUNCH((pick_token<false, false, false>), g2, s, v); }
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_export_p_rows(dssd_ctx* c, const dssd_batch* b, void* p_rows, int32_t p_dtype,
+                                          void* hip_stream) {
+  BatchView v;
+  const dssd_status st = check_and_view(c, b, nullptr, &v, false);
+  if (st != DSSD_OK || b->B == 0) return st;
+  if (b->total_drafts == 0) return DSSD_OK;
+  if (!p_rows || (p_dtype != DSSD_F32 && p_dtype != DSSD_F16)) return DSSD_EINVAL;
+  const bool f16 = p_dtype == DSSD_F16;
+  if (reinterpret_cast<uintptr_t>(p_rows) % (f16 ? 2 : 4)) return DSSD_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool bf16 = b->logits_dtype == DSSD_BF16;
+  const bool al = vector_ok(b) && (reinterpret_cast<uintptr_t>(p_rows) & 15) == 0;
+  const int32_t groups = (v.C + 3) / 4;
+  if ((int64_t)groups * b->B > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+  const unsigned grid = (unsigned)(groups * b->B);
+  {
+    Timed t(c, DSSD_K_EXPORT_P, s);
+#define DSSD_EXPORT(BF, AL, H) DSSD_LAUNCH((export_p_rows<BF, AL, H>), grid, s, v, groups, p_rows)
+    if (bf16) { if (al) { if (f16) DSSD_EXPORT(true, true, true); else DSSD_EXPORT(true, true, false); }
+                else    { if (f16) DSSD_EXPORT(true, false, true); else DSSD_EXPORT(true, false, false); } }
+    else      { if (al) { if (f16) DSSD_EXPORT(false, true, true); else DSSD_EXPORT(false, true, false); }
+                else    { if (f16) DSSD_EXPORT(false, false, true); else DSSD_EXPORT(false, false, false); } }
+#undef DSSD_EXPORT
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_device_batch* b, void* hip_stream) {
+  if (!c || !b) return DSSD_EINVAL;
+  if (b->B < 0 || b->V < 1 || b->gamma < 0 || b->total_drafts < 0) return DSSD_EINVAL;
+  if (b->p_dtype != DSSD_F32 && b->p_dtype != DSSD_F16) return DSSD_EINVAL;
+  if (!b->draft_offsets && b->total_drafts != (int64_t)b->B * b->gamma) return DSSD_EINVAL;
+  if (b->B == 0 || b->total_drafts == 0) return DSSD_OK;
+  if (!b->draft_probs || !b->p_rows || !b->accepted_len || !b->rejected || !b->out_token) return DSSD_EINVAL;
+  const bool f16 = b->p_dtype == DSSD_F16;
+  auto mis = [](const void* p, uintptr_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) != 0; };
+  if (mis(b->draft_probs, 4) || mis(b->p_rows, f16 ? 2 : 4) || mis(b->draft_offsets, 4) || mis(b->accepted_len, 4) ||
+      mis(b->rejected, 4) || mis(b->out_token, 4) || mis(b->status, 4))
+    return DSSD_EALIGN;
+  DeviceView d;
+  d.B = b->B; d.V = b->V; d.gamma = b->gamma; d.C = (b->V + 4095) / 4096; d.R_Q = b->total_drafts;
+  if (b->B > c->max_rows || b->V > c->max_V || d.C > c->max_C) return DSSD_ENOMEM;
+  d.offsets = b->draft_offsets; d.draft_probs = b->draft_probs; d.p_rows = b->p_rows;
+  d.accepted_len = b->accepted_len; d.rejected = b->rejected;
+  d.seed_lo = (uint32_t)b->seed; d.seed_hi = (uint32_t)(b->seed >> 32);
+  d.step_lo = (uint32_t)b->step; d.step_hi = (uint32_t)(b->step >> 32);
+  d.session_base = b->session_base;
+  d.out_token = b->out_token; d.status = b->status; d.resid_mass = c->resid_mass;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool al = (b->V % 8) == 0 && (reinterpret_cast<uintptr_t>(b->p_rows) & 15) == 0 &&
+                  (reinterpret_cast<uintptr_t>(b->draft_probs) & 15) == 0;
+  const int32_t groups = (d.C + 3) / 4;
+  if ((int64_t)groups * b->B > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+  {
+    Timed t(c, DSSD_K_DEVICE_MASS, s);
+    const unsigned grid = (unsigned)(groups * b->B);
+    if (f16) { if (al) DSSD_LAUNCH((device_resid_mass<true, true>), grid, s, d, groups); else DSSD_LAUNCH((device_resid_mass<true, false>), grid, s, d, groups); }
+    else     { if (al) DSSD_LAUNCH((device_resid_mass<false, true>), grid, s, d, groups); else DSSD_LAUNCH((device_resid_mass<false, false>), grid, s, d, groups); }
+  }
+  {
+    Timed t(c, DSSD_K_DEVICE_PICK, s);
+    const unsigned g2 = (unsigned)((b->B + 3) / 4);
+    if (f16) { if (al) DSSD_LAUNCH((device_pick<true, true>), g2, s, d); else DSSD_LAUNCH((device_pick<true, false>), g2, s, d); }
+    else     { if (al) DSSD_LAUNCH((device_pick<false, true>), g2, s, d); else DSSD_LAUNCH((device_pick<false, false>), g2, s, d); }
   }
   return launch_status();
 }

@@ -27,7 +27,8 @@ struct BatchView {
   int64_t R_L, R_Q;
   const int32_t* offsets;            // may be null
   const void* logits;
-  const float* draft_probs;
+  const float* draft_probs;          // may be null when q_scalars is given (verify only)
+  const float* q_scalars;            // [R_Q] q_i(x_i) as uploaded by the device, or null
   const int32_t* tokens;
   const float* inv_temp;             // may be null
   uint32_t seed_lo, seed_hi, step_lo, step_hi, session_base;
@@ -193,7 +194,7 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
             } else {
               const float zx = load_logit(logits_row<BF16>(a, lrow), x, BF16);
               p = fast_exp2(fmaf(zx, c1, -st.x)) / st.y;
-              q = a.draft_probs[qrow * (int64_t)a.V + x];
+              q = a.q_scalars ? a.q_scalars[qrow] : a.draft_probs[qrow * (int64_t)a.V + x];
               const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)i, a.step_lo, a.step_hi, a.seed_lo,
                                a.seed_hi);
               const float r = u01(rnd.w[0]);
@@ -265,6 +266,15 @@ __device__ __forceinline__ float group_weights(const char* lrow, const float* qr
   return sum;
 }
 
+template <bool BF16, bool ALIGNED, bool RESID>
+struct LogitWeights {
+  static constexpr int E = Elems<BF16>::per_vec;
+  const char* lp; const float* qp; int32_t V; float c1, M2, invZ;
+  __device__ __forceinline__ float group(int64_t vec, float* w) const {
+    return group_weights<BF16, ALIGNED, RESID>(lp, qp, vec, V, c1, M2, invZ, w);
+  }
+};
+
 // Residual mass per chunk of the rejected row, one wave per chunk; sessions that were not
 // rejected exit at once.
 template <bool BF16, bool ALIGNED>
@@ -309,16 +319,17 @@ __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t gro
 // The wave scans the chunk's 8 sub-blocks of 64 groups; at each level (sub-block, lane, element)
 // the local target is clamped into [0, local total) so that a token is always found and a
 // zero-weight token never is.
-template <bool BF16, bool ALIGNED, bool RESID>
-__device__ __forceinline__ int32_t pick_in_chunk(const char* lp, const float* qp, int32_t V, int32_t c,
-                                                 float c1, float M2, float invZ, float target, int lane) {
-  constexpr int E = Elems<BF16>::per_vec;
+// `wf.group(g, w)` fills the W::E weights of group g of the row and returns their sum (summed in
+// element order); the same functor must have produced the chunk masses.
+template <typename W>
+__device__ __forceinline__ int32_t pick_in_chunk(const W& wf, int32_t c, float target, int lane) {
+  constexpr int E = W::E;
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
   float lsum[kUnroll], scan[kUnroll], S[kUnroll];
 #pragma unroll
   for (int k = 0; k < kUnroll; ++k) {
     float w[E];
-    lsum[k] = group_weights<BF16, ALIGNED, RESID>(lp, qp, v0 + k * kWave, V, c1, M2, invZ, w);
+    lsum[k] = wf.group(v0 + k * kWave, w);
     scan[k] = wave_scan(lsum[k], lane);
     S[k] = lane_value(scan[k], 63);
   }
@@ -353,7 +364,7 @@ __device__ __forceinline__ int32_t pick_in_chunk(const char* lp, const float* qp
   if (lane == lsel) {
     float w[E];
     const int64_t vec = v0 + (int64_t)ksel * kWave;
-    group_weights<BF16, ALIGNED, RESID>(lp, qp, vec, V, c1, M2, invZ, w);
+    wf.group(vec, w);
     float pre = 0.f;
     int esel = E - 1;
     bool hit = false;
@@ -427,12 +438,12 @@ __global__ __launch_bounds__(256) void pick_token(const BatchView a) {
   if constexpr (RESID) {
     const float* rm = a.resid_mass + (int64_t)b * a.C;
     const int32_t c = pick_chunk([&](int32_t cc) { return rm[cc]; }, a.C, r, lane, &target, &total);
-    if (c >= 0) token = pick_in_chunk<BF16, ALIGNED, true>(lp, qp, a.V, c, c1, st.x, invZ, target, lane);
+    if (c >= 0) token = pick_in_chunk(LogitWeights<BF16, ALIGNED, true>{lp, qp, a.V, c1, st.x, invZ}, c, target, lane);
     if (token < 0) from_p = true;   // residual mass rounded to zero: draw from P_n instead
   }
   if (from_p) {
     const int32_t c = pick_chunk(p_mass, a.C, r, lane, &target, &total);
-    if (c >= 0) token = pick_in_chunk<BF16, ALIGNED, false>(lp, nullptr, a.V, c, c1, st.x, invZ, target, lane);
+    if (c >= 0) token = pick_in_chunk(LogitWeights<BF16, ALIGNED, false>{lp, nullptr, a.V, c1, st.x, invZ}, c, target, lane);
   }
   if (lane == 0) {
     a.out_token[b] = token;

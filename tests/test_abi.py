@@ -35,14 +35,20 @@ def test_struct_layout_matches_the_header(tmp_path):
     src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "dssd.h"\nint main(void){\n'
                    'printf("%zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(dssd_batch), offsetof(dssd_batch, total_drafts),'
                    ' offsetof(dssd_batch, logits), offsetof(dssd_batch, seed), offsetof(dssd_batch, session_base),'
-                   ' sizeof(dssd_out), offsetof(dssd_out, row_stats), offsetof(dssd_out, status));return 0;}\n')
+                   ' sizeof(dssd_out), offsetof(dssd_out, row_stats), offsetof(dssd_out, status));'
+                   'printf("%zu %zu %zu %zu %zu %zu\\n", offsetof(dssd_batch, draft_q_tok), sizeof(dssd_device_batch),'
+                   ' offsetof(dssd_device_batch, p_rows), offsetof(dssd_device_batch, seed),'
+                   ' offsetof(dssd_device_batch, out_token), offsetof(dssd_device_batch, status));return 0;}\n')
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
                    check=True)
     got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     want = [C.sizeof(D.dssd_batch), D.dssd_batch.total_drafts.offset, D.dssd_batch.logits.offset,
             D.dssd_batch.seed.offset, D.dssd_batch.session_base.offset, C.sizeof(D.dssd_out),
-            D.dssd_out.row_stats.offset, D.dssd_out.status.offset]
+            D.dssd_out.row_stats.offset, D.dssd_out.status.offset,
+            D.dssd_batch.draft_q_tok.offset, C.sizeof(D.dssd_device_batch), D.dssd_device_batch.p_rows.offset,
+            D.dssd_device_batch.seed.offset, D.dssd_device_batch.out_token.offset,
+            D.dssd_device_batch.status.offset]
     assert got == want
 
 

@@ -1,0 +1,261 @@
+"""GPU parity of the DSSD split proper (Sec. 3, Algorithm 2): the edge verifying from the
+uploaded scalars q_i(x_i), the downlink export of P_j in 32 / 16 bit, and the device redrawing
+from the received row -- each against the CPU oracle's edge / device functions."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle as O                  # noqa: E402
+from paper_2507_12000_amd import binding as D   # noqa: E402
+from paper_2507_12000_amd import synth          # noqa: E402
+import parity                                   # noqa: E402
+
+DEV = "cuda:0"
+TIE = parity.TIE
+
+CASES = [
+    synth.Workload("split_bf16_ragged", B=37, V=4096 * 3 + 264, gamma=0, dtype="bf16", gamma_range=(1, 9),
+                   sigmas=(1.0, 2.0), temperature_range=(0.6, 1.4), frac_q_uniform=0.1),
+    synth.Workload("split_f32", B=19, V=10000, gamma=4, dtype="f32", sigmas=(0.2, 1.5)),
+    synth.Workload("split_bf16_unaligned", B=11, V=9001, gamma=3, dtype="bf16", sigmas=(0.2, 1.5)),
+    synth.Workload("split_f32_unaligned", B=9, V=5003, gamma=2, dtype="f32", sigmas=(0.2, 2.0)),
+]
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = D.Context(DEV, max_rows=4096, max_V=152064)
+    yield c
+    c.close()
+
+
+def q_scalars_of(inputs):
+    rows = torch.arange(inputs["R_Q"], device=DEV)
+    return inputs["draft_probs"][rows, inputs["draft_tokens"].long()].contiguous()
+
+
+def run_edge(ctx, inputs, seed, step, p_dtype):
+    """verify (from q scalars) + bonus + export on the GPU."""
+    qs = q_scalars_of(inputs)
+    batch = D.make_batch(inputs, seed=seed, step=step, q_scalars=qs)
+    t, out = D.alloc_out(inputs, DEV)
+    s = ctx.stream()
+    D.dssd_verify_batch(ctx.handle, batch, out, s)
+    D.dssd_bonus_sample(ctx.handle, batch, out, s)
+    p_rows = torch.full((inputs["B"], inputs["V"]), -1.0, device=DEV,
+                        dtype=torch.float16 if p_dtype == D.DSSD_F16 else torch.float32)
+    D.dssd_export_p_rows(ctx.handle, batch, p_rows.data_ptr(), p_dtype, s)
+    torch.cuda.synchronize()
+    return t, p_rows, qs, batch, out
+
+
+def weights_valid(w, r, token):
+    c = np.cumsum(w)
+    t, R = r * c[-1], c[-1]
+    lo = c[token - 1] if token > 0 else 0.0
+    return w[token] > 0 and lo - TIE * R <= t < c[token] + TIE * R
+
+
+@pytest.mark.parametrize("w", CASES, ids=[w.name for w in CASES])
+def test_edge_from_q_scalars(ctx, w):
+    inputs = synth.generate(w, seed=3, device=DEV)
+    seed, step = 11, 2
+    # reference on the GPU: the same step fed with the full Q rows
+    full_t, full_out = D.alloc_out(inputs, DEV)
+    fb = D.make_batch(inputs, seed=seed, step=step)
+    ctx.step(fb, full_out)
+    torch.cuda.synchronize()
+    t, p_rows, qs, _, _ = run_edge(ctx, inputs, seed, step, D.DSSD_F32)
+    for k in ("accepted_len", "rejected", "p_tok", "q_tok", "row_stats"):
+        assert torch.equal(t[k], full_t[k]), k
+    rej = t["rejected"].bool()
+    assert torch.equal(t["out_token"][~rej], full_t["out_token"][~rej])       # bonus tokens
+    assert (t["out_token"][rej] == -7).all()                                  # the edge does not redraw
+    assert rej.any() and (~rej).any()
+    # against the oracle's edge
+    h = parity.to_numpy_inputs(inputs)
+    e = O.edge_batch(h["logits"], h["dtype"], qs.cpu().numpy(), h["draft_tokens"], w.V, O.P_F32, gamma=h["gamma"],
+                     draft_offsets=h["draft_offsets"], inv_temperature=h["inv_temperature"], seed=seed, step=step, B=w.B)
+    g_n, g_rej, g_tok = (t[k].cpu().numpy() for k in ("accepted_len", "rejected", "out_token"))
+    for b in range(w.B):
+        r = e["res"][b]
+        if r["accept_margin"] < TIE:
+            continue
+        assert (g_n[b], g_rej[b]) == (r["n"], r["rejected"]), b
+        if not r["rejected"] and r["cdf_margin"] >= TIE:
+            assert g_tok[b] == r["token"], b
+
+
+@pytest.mark.parametrize("w", CASES, ids=[w.name for w in CASES])
+@pytest.mark.parametrize("p_dtype", [D.DSSD_F32, D.DSSD_F16])
+def test_export_p_rows(ctx, w, p_dtype):
+    inputs = synth.generate(w, seed=4, device=DEV)
+    seed, step = 5, 0
+    t, p_rows, qs, _, _ = run_edge(ctx, inputs, seed, step, p_dtype)
+    h = parity.to_numpy_inputs(inputs)
+    o_dtype = O.P_F16 if p_dtype == D.DSSD_F16 else O.P_F32
+    e = O.edge_batch(h["logits"], h["dtype"], qs.cpu().numpy(), h["draft_tokens"], w.V, o_dtype, gamma=h["gamma"],
+                     draft_offsets=h["draft_offsets"], inv_temperature=h["inv_temperature"], seed=seed, step=step, B=w.B)
+    g_rej = t["rejected"].cpu().numpy()
+    rows = p_rows.cpu()
+    checked = 0
+    for b in range(w.B):
+        r = e["res"][b]
+        if r["accept_margin"] < TIE:
+            continue
+        assert g_rej[b] == r["rejected"]
+        if not g_rej[b]:
+            assert (rows[b] == -1.0).all()            # untouched
+            continue
+        checked += 1
+        if p_dtype == D.DSSD_F32:
+            want = e["p_rows"][b].astype(np.float64)
+            got = rows[b].numpy().astype(np.float64)
+            big = want > 1e-30
+            assert (np.abs(got[big] - want[big]) <= 1e-5 * want[big]).all()
+            assert (got[~big] <= 2e-30).all()
+            assert abs(got.sum() - 1.0) < 1e-4
+        else:
+            want = e["p_rows"][b].astype(np.int64)                    # binary16 codes of positive values
+            got = rows[b].view(torch.int16).numpy().astype(np.int64)
+            diff = np.abs(got - want)
+            # the two sides round fp32 values that differ by ~1e-6 relative: a value next to a
+            # rounding boundary may land on the neighbouring code, never further
+            assert diff.max() <= 1, (b, diff.max())
+            assert (diff != 0).mean() < 1e-2, (b, (diff != 0).mean())
+    assert checked > 0
+
+
+def _device_case(w, p_torch_dtype, seed):
+    """Seeded synthetic input of the device call alone: Q rows from the generator, received rows
+    P~ = softmax of the generator's logits rounded to the downlink type, j drawn at random."""
+    inputs = synth.generate(w, seed=seed, device=DEV)
+    g = torch.Generator(device=DEV); g.manual_seed(seed + 99)
+    off = inputs["draft_offsets"]
+    B = w.B
+    gam = (off[1:] - off[:-1]) if off is not None else torch.full((B,), w.gamma, device=DEV, dtype=torch.int32)
+    first = off[:-1].long() if off is not None else torch.arange(B, device=DEV) * w.gamma
+    rejected = ((torch.rand(B, generator=g, device=DEV) < 0.7) & (gam > 0)).to(torch.int32)
+    n = (torch.rand(B, generator=g, device=DEV) * gam.clamp(min=1)).long().clamp(max=(gam.long() - 1).clamp(min=0))
+    lrow = first + torch.arange(B, device=DEV) + n
+    tau = inputs["inv_temperature"] if inputs["inv_temperature"] is not None else torch.ones(B, device=DEV)
+    P = torch.softmax(inputs["logits"][lrow].float() * tau[:, None], dim=1)
+    return inputs, P.to(p_torch_dtype).contiguous(), n.to(torch.int32), rejected
+
+
+@pytest.mark.parametrize("w", CASES, ids=[w.name for w in CASES])
+@pytest.mark.parametrize("p_torch_dtype", [torch.float32, torch.float16])
+def test_device_redraw_from_received_rows(ctx, w, p_torch_dtype):
+    inputs, p_rows, n, rejected = _device_case(w, p_torch_dtype, seed=6)
+    B = w.B
+    # two degenerate sessions: a record outside the session, and P~ == Q (no residual mass)
+    rej_idx = torch.nonzero(rejected).flatten().tolist()
+    assert len(rej_idx) >= 3
+    b_bad, b_zero = rej_idx[0], rej_idx[1]
+    n[b_bad] = 99
+    off = inputs["draft_offsets"]
+    first_zero = int(off[b_zero]) if off is not None else b_zero * w.gamma
+    p_rows[b_zero] = inputs["draft_probs"][first_zero + int(n[b_zero])].to(p_torch_dtype)
+    if p_torch_dtype == torch.float16:   # make P~ <= Q hold exactly after rounding
+        inputs["draft_probs"][first_zero + int(n[b_zero])] = p_rows[b_zero].float()
+    out_token = torch.full((B,), -7, device=DEV, dtype=torch.int32)
+    status = torch.full((B,), -7, device=DEV, dtype=torch.int32)
+    seed, step, base = 21, 8, 5000
+    db = D.make_device_batch(inputs, p_rows, n, rejected, out_token, status, seed=seed, step=step, session_base=base)
+    D.dssd_residual_sample_from_p(ctx.handle, db, ctx.stream())
+    torch.cuda.synchronize()
+    h = parity.to_numpy_inputs(inputs)
+    o_dtype = O.P_F16 if p_torch_dtype == torch.float16 else O.P_F32
+    rows_np = p_rows.view(torch.int16).cpu().numpy().view(np.uint16) if p_torch_dtype == torch.float16 else p_rows.cpu().numpy()
+    orc = O.device_batch(h["draft_probs"], rows_np, o_dtype, n.cpu().numpy(), rejected.cpu().numpy(), w.V,
+                         gamma=h["gamma"], draft_offsets=h["draft_offsets"], seed=seed, step=step, session_base=base)
+    g_tok, g_st = out_token.cpu().numpy(), status.cpu().numpy()
+    rj = rejected.cpu().numpy()
+    ties = 0
+    for b in range(B):
+        if not rj[b]:
+            assert g_tok[b] == -7 and g_st[b] == -7          # untouched
+            continue
+        if b == b_bad:
+            assert g_tok[b] == -1 and g_st[b] == D.SESSION_BAD_OFFSETS and orc["status"][b] == 4
+            continue
+        assert g_st[b] == orc["status"][b], (b, g_st[b], orc["status"][b])
+        if b == b_zero:
+            assert g_st[b] == D.SESSION_ZERO_RESIDUAL
+        if g_tok[b] != orc["token"][b]:
+            assert orc["cdf_margin"][b] < TIE, (b, g_tok[b], orc["token"][b], orc["cdf_margin"][b])
+            first = int(h["draft_offsets"][b]) if h["draft_offsets"] is not None else b * w.gamma
+            Pd = rows_np[b].view(np.float16).astype(np.float64) if o_dtype == O.P_F16 else rows_np[b].astype(np.float64)
+            wts = Pd if orc["status"][b] & 2 else np.maximum(0.0, Pd - h["draft_probs"][first + int(n[b])].astype(np.float64))
+            r = O.u01(O.random_block(seed, step, base + b, int(n[b]))[1])
+            assert weights_valid(wts, r, int(g_tok[b])), b
+            ties += 1
+    assert ties <= max(2, B // 20)
+
+
+@pytest.mark.parametrize("p_dtype", [D.DSSD_F32, D.DSSD_F16])
+def test_split_end_to_end_matches_oracle_chain(ctx, p_dtype):
+    """edge (q scalars) -> export -> device on the GPU against the same chain in the oracle."""
+    w = synth.Workload("chain", B=64, V=32000, gamma=4, dtype="bf16", sigmas=(1.0, 2.0))
+    inputs = synth.generate(w, seed=9, device=DEV)
+    seed, step = 33, 6
+    t, p_rows, qs, _, _ = run_edge(ctx, inputs, seed, step, p_dtype)
+    out_token = t["out_token"]
+    db = D.make_device_batch(inputs, p_rows, t["accepted_len"], t["rejected"], out_token, None, seed=seed, step=step)
+    D.dssd_residual_sample_from_p(ctx.handle, db, ctx.stream())
+    torch.cuda.synchronize()
+    h = parity.to_numpy_inputs(inputs)
+    o_dtype = O.P_F16 if p_dtype == D.DSSD_F16 else O.P_F32
+    e = O.edge_batch(h["logits"], h["dtype"], qs.cpu().numpy(), h["draft_tokens"], w.V, o_dtype, gamma=w.gamma,
+                     seed=seed, step=step, B=w.B)
+    dv = O.device_batch(h["draft_probs"], e["p_rows"], o_dtype, e["res"]["n"], e["res"]["rejected"], w.V,
+                        gamma=w.gamma, seed=seed, step=step)
+    want = np.where(e["res"]["rejected"] == 1, dv["token"], e["res"]["token"])
+    got = out_token.cpu().numpy()
+    assert ((got >= 0) & (got < w.V)).all()
+    differ = 0
+    for b in range(w.B):
+        if e["res"][b]["accept_margin"] < TIE:
+            continue
+        if got[b] != want[b]:
+            margin = dv["cdf_margin"][b] if e["res"][b]["rejected"] else e["res"][b]["cdf_margin"]
+            assert margin < TIE, (b, got[b], want[b], margin)
+            differ += 1
+    assert differ <= 3
+    # Against the unsplit step (exact P): a 32-bit downlink draws the same tokens; a 16-bit one
+    # shifts the CDF by the mass lost below binary16's range, so draws that land in low-mass
+    # tokens move to a neighbour (the law barely changes, the coupled sample does).
+    full_t, full_out = D.alloc_out(inputs, DEV)
+    ctx.step(D.make_batch(inputs, seed=seed, step=step), full_out)
+    torch.cuda.synchronize()
+    full_tok = full_t["out_token"].cpu().numpy()
+    same = (full_tok == got).mean()
+    print(f"[split] p_dtype={p_dtype}: {same:.3f} of tokens equal the unsplit step's", flush=True)
+    assert same > (0.5 if p_dtype == D.DSSD_F16 else 0.97), same
+    acc = e["res"]["rejected"] == 0
+    assert (full_tok[acc] == got[acc]).all()          # bonus tokens never depend on the downlink type
+
+
+def test_split_calls_reject_bad_arguments(ctx):
+    w = CASES[1]
+    inputs = synth.generate(w, seed=1, device=DEV)
+    t, p_rows, qs, batch, out = run_edge(ctx, inputs, 1, 1, D.DSSD_F32)
+    assert D.dssd_export_p_rows(ctx.handle, batch, 0, D.DSSD_F32, 0, check=False) == D.DSSD_EINVAL
+    assert D.dssd_export_p_rows(ctx.handle, batch, p_rows.data_ptr(), D.DSSD_BF16, 0, check=False) == D.DSSD_EINVAL
+    assert D.dssd_export_p_rows(ctx.handle, batch, p_rows.data_ptr() + 2, D.DSSD_F32, 0, check=False) == D.DSSD_EALIGN
+    # the residual from logits needs the Q rows, which this batch does not carry
+    assert D.dssd_residual_sample(ctx.handle, batch, out, 0, check=False) == D.DSSD_EINVAL
+    db = D.make_device_batch(inputs, p_rows, t["accepted_len"], t["rejected"], t["out_token"])
+    db.p_dtype = D.DSSD_BF16
+    assert D.dssd_residual_sample_from_p(ctx.handle, db, 0, check=False) == D.DSSD_EINVAL
+    db = D.make_device_batch(inputs, p_rows, t["accepted_len"], t["rejected"], t["out_token"])
+    db.p_rows = None
+    assert D.dssd_residual_sample_from_p(ctx.handle, db, 0, check=False) == D.DSSD_EINVAL
+    db = D.make_device_batch(inputs, p_rows, t["accepted_len"], t["rejected"], t["out_token"])
+    db.V = 152065
+    assert D.dssd_residual_sample_from_p(ctx.handle, db, 0, check=False) == D.DSSD_ENOMEM
+    assert D.load().dssd_residual_sample_from_p(None, None, None) == D.DSSD_EINVAL
+    torch.cuda.synchronize()
