@@ -100,8 +100,59 @@ def cpu_baseline(inputs, seed, budget_s=12.0):
             "rows_per_s": (pos + n) / t}
 
 
+def time_split_path(ctx, D, torch, inputs, outs, args, kernels_of):
+    """The same batch through the paper's split: the edge verifies from the uploaded scalars
+    q_i(x_i) and draws bonus tokens, exports P_n of every rejected session as fp16 (the downlink
+    payload), and the device redraws from the received rows and its own Q rows.  Reported beside
+    the headline figure, never as `value`."""
+    dev = outs["rejected"].device
+    rows = torch.arange(inputs["R_Q"], device=dev)
+    qs = inputs["draft_probs"][rows, inputs["draft_tokens"].long()].contiguous()
+    batch = D.make_batch(inputs, seed=args.seed, step=0, q_scalars=qs)
+    out = D.dssd_out(accepted_len=outs["accepted_len"].data_ptr(), rejected=outs["rejected"].data_ptr(),
+                     out_token=outs["out_token"].data_ptr())
+    p_rows = torch.empty((inputs["B"], inputs["V"]), device=dev, dtype=torch.float16)
+    dbatch = D.make_device_batch(inputs, p_rows, outs["accepted_len"], outs["rejected"], outs["out_token"],
+                                 seed=args.seed, step=0)
+    s = ctx.stream()
+
+    def one(step):
+        batch.step = step
+        dbatch.step = step
+        D.dssd_verify_batch(ctx.handle, batch, out, s)
+        D.dssd_bonus_sample(ctx.handle, batch, out, s)
+        D.dssd_export_p_rows(ctx.handle, batch, p_rows.data_ptr(), D.DSSD_F16, s)
+        D.dssd_residual_sample_from_p(ctx.handle, dbatch, s)
+
+    for k in range(args.warmup):
+        one(k)
+    torch.cuda.synchronize()
+    D.dssd_profile_reset(ctx.handle)
+    D.dssd_profile_enable(ctx.handle, True)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one(args.warmup + k)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    D.dssd_profile_enable(ctx.handle, False)
+    ks = {name: 1e3 * ms / max(n, 1) for name, (ms, n) in kernels_of().items() if n}
+    n_rej = int(outs["rejected"].sum().item())
+    V, s_L = inputs["V"], inputs["logits"].element_size()
+    export_bytes = n_rej * V * (s_L + 2)          # read the logits row, write the fp16 row
+    device_bytes = n_rej * V * (2 + 4)            # read the fp16 row and the Q row
+    return {"ms_per_step": 1e3 * elapsed / args.steps,
+            "positions_per_sec": inputs["R_Q"] * args.steps / elapsed,
+            "downlink": "fp16", "rejected_sessions": n_rej, "kernels_avg_us": ks,
+            "export_p_rows_GBps": export_bytes / (ks["export_p_rows"] * 1e-6) / 1e9 if "export_p_rows" in ks else None,
+            "device_resid_mass_GBps": device_bytes / (ks["device_resid_mass"] * 1e-6) / 1e9
+            if "device_resid_mass" in ks else None,
+            "downlink_bytes_per_rejected_session": V * 2, "uplink_bytes_per_position": 8}
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--split", action="store_true",
+                    help="also time the edge/device split path (q scalars up, fp16 P rows down)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
@@ -191,6 +242,9 @@ def main():
                      "traffic": traffic, "algorithmic_bytes_per_launch": ab["row_stats"],
                      "avg_launch_us": k1_us},
     }
+    if args.split:
+        result["split_path"] = time_split_path(ctx, D, torch, inputs, outs, args, kernels_of=lambda: {
+            D.kernel_name(k): D.dssd_profile_read(ctx.handle, k) for k in range(D.K_COUNT)})
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inputs, args.seed, budget_s=15.0)
     ctx.close()
