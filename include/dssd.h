@@ -172,8 +172,9 @@ const char *dssd_status_str(dssd_status s);
 
 /* Kernel timing (measurement aid, not on the hot path).  While enabled, every kernel launch is
  * bracketed by HIP events on the launch stream.  Kernel ids: 0 row softmax statistics,
- * 1 accept / first-reject, 2 residual chunk masses, 3 residual pick, 4 bonus pick, 5 export of
- * P rows, 6 and 7 chunk masses and pick of the device-side redraw. */
+ * 1 accept / first-reject, 2 residual chunk masses (for small batches also the pick, in one
+ * launch), 3 residual pick, 4 bonus pick, 5 export of P rows, 6 and 7 chunk masses and pick of
+ * the device-side redraw. */
 enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
        DSSD_K_BONUS_PICK = 4, DSSD_K_EXPORT_P = 5, DSSD_K_DEVICE_MASS = 6, DSSD_K_DEVICE_PICK = 7,
        DSSD_K_COUNT = 8 };

@@ -22,6 +22,7 @@ struct dssd_ctx {
   float* resid_mass = nullptr;
   Job* resid_job = nullptr;
   Job* bonus_job = nullptr;
+  int32_t* arrive_resid = nullptr;
   bool profiling = false;
   std::vector<hipEvent_t> ev_begin[DSSD_K_COUNT], ev_end[DSSD_K_COUNT];
   size_t ev_used[DSSD_K_COUNT] = {};
@@ -38,7 +39,8 @@ extern "C" size_t dssd_workspace_bytes(int64_t max_rows, int32_t max_V, int32_t 
   const size_t C = (size_t)chunks_per_row(max_V, logits_dtype);
   const size_t rows = (size_t)max_rows;
   return align256(rows * C * sizeof(float2)) + align256(rows * sizeof(float2)) +
-         align256(rows * C * sizeof(float)) + 2 * align256(rows * sizeof(Job));
+         align256(rows * C * sizeof(float)) + 2 * align256(rows * sizeof(Job)) +
+         align256(rows * sizeof(int32_t));
 }
 
 extern "C" const char* dssd_status_str(dssd_status s) {
@@ -84,7 +86,14 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   c->row_tab = reinterpret_cast<float2*>(p);     p += align256(rows * sizeof(float2));
   c->resid_mass = reinterpret_cast<float*>(p);   p += align256(rows * C * sizeof(float));
   c->resid_job = reinterpret_cast<Job*>(p);      p += align256(rows * sizeof(Job));
-  c->bonus_job = reinterpret_cast<Job*>(p);
+  c->bonus_job = reinterpret_cast<Job*>(p);      p += align256(rows * sizeof(Job));
+  c->arrive_resid = reinterpret_cast<int32_t*>(p);
+  // arrival counters start at zero; every kernel that uses them leaves them at zero
+  if (hipMemset(c->arrive_resid, 0, rows * sizeof(int32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    (void)hipFree(c->workspace);
+    delete c;
+    return DSSD_EHIP;
+  }
   *out = c;
   return DSSD_OK;
 }
@@ -133,7 +142,7 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   v->accepted_len = o->accepted_len; v->rejected = o->rejected; v->out_token = o->out_token;
   v->row_stats = o->row_stats; v->p_tok = o->p_tok; v->q_tok = o->q_tok; v->status = o->status;
   v->chunk_stats = c->chunk_stats; v->row_tab = c->row_tab; v->resid_mass = c->resid_mass;
-  v->resid_job = c->resid_job; v->bonus_job = c->bonus_job;
+  v->resid_job = c->resid_job; v->bonus_job = c->bonus_job; v->arrive_resid = c->arrive_resid;
   return DSSD_OK;
 }
 
@@ -203,12 +212,17 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   const int32_t groups = (v.C + 3) / 4;
   if ((int64_t)groups * b->B > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
   const unsigned grid = (unsigned)(groups * b->B);
+  // Few chunk waves: one launch, the last wave of each session draws the token.  Many: two.
+  const bool fuse = (int64_t)b->B * v.C <= 4096;
   {
     Timed t(c, DSSD_K_RESID_MASS, s);
-    if (bf16) { if (al) DSSD_LAUNCH((resid_mass<true, true>), grid, s, v, groups); else DSSD_LAUNCH((resid_mass<true, false>), grid, s, v, groups); }
-    else      { if (al) DSSD_LAUNCH((resid_mass<false, true>), grid, s, v, groups); else DSSD_LAUNCH((resid_mass<false, false>), grid, s, v, groups); }
+#define DSSD_RESID(BF, AL) do { if (fuse) DSSD_LAUNCH((resid_mass<BF, AL, true>), grid, s, v, groups); \
+                                else DSSD_LAUNCH((resid_mass<BF, AL, false>), grid, s, v, groups); } while (0)
+    if (bf16) { if (al) DSSD_RESID(true, true); else DSSD_RESID(true, false); }
+    else      { if (al) DSSD_RESID(false, true); else DSSD_RESID(false, false); }
+#undef DSSD_RESID
   }
-  {
+  if (!fuse) {
     Timed t(c, DSSD_K_RESID_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     if (bf16) { if (al) DSSD_LAUNCH((pick_token<true, true, true>), g2, s, v); else DSSD_LAUNCH((pick_token<true, false, true>), g2, s, v); }

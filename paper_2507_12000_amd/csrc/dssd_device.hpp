@@ -146,6 +146,22 @@ __device__ __forceinline__ void load_probs(const float* row, int64_t e0, int32_t
   }
 }
 
+// ------------------------------------------------------------------ cross-workgroup hand-over
+// A value written by one workgroup and read by another inside the same launch.  publish()
+// writes it through to the device-coherent level, arrive() waits for this wave's published
+// stores to complete and then bumps a counter, observe() reads at the device-coherent level.
+// No cache-wide write-back or invalidate is involved, so streaming waves are not disturbed.
+__device__ __forceinline__ void publish(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float observe(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t arrive(int32_t* counter) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's stores have completed
+  return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Consecutive workgroup ids are dealt round-robin to the chip's 8 XCDs.  This maps a hardware
 // workgroup id to a logical one so that each XCD walks one contiguous eighth of the work (and
 // of the address range) instead of every eighth block of it.

@@ -46,6 +46,7 @@ struct BatchView {
   float* resid_mass;                 // [B, C]
   Job* resid_job;                    // [B] rejected sessions: row n
   Job* bonus_job;                    // [B] all-accepted sessions: row gamma_b
+  int32_t* arrive_resid;             // [B] chunk masses finished per session; zero between calls
 };
 
 __device__ __forceinline__ int64_t session_first_draft(const BatchView& a, int32_t b) {
@@ -275,9 +276,15 @@ struct LogitWeights {
   }
 };
 
-// Residual mass per chunk of the rejected row, one wave per chunk; sessions that were not
-// rejected exit at once.
-template <bool BF16, bool ALIGNED>
+template <bool BF16, bool ALIGNED, bool RESID>
+__device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, int lane);
+
+// Residual resample (Algorithm 2 "Resample"): mass of max(0, P - Q) per chunk of the rejected
+// row, one wave per chunk.  Sessions that were not rejected exit at once.  FUSE_PICK: the last
+// wave of a session to finish also draws the token, which saves the second launch -- worth it
+// for small batches only (measured: the per-wave arrival costs more than a launch once there
+// are more than a few thousand chunk waves).
+template <bool BF16, bool ALIGNED, bool FUSE_PICK>
 __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t groups) {
   constexpr int E = Elems<BF16>::per_vec;
   const int lane = threadIdx.x & 63;
@@ -312,7 +319,22 @@ __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t gro
         acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z[k][e], c1, -st.x)), invZ, -q[k][e]));
   }
   acc = wave_sum(acc);
-  if (lane == 0) a.resid_mass[(int64_t)b * a.C + c] = acc;
+  if constexpr (!FUSE_PICK) {
+    if (lane == 0) a.resid_mass[(int64_t)b * a.C + c] = acc;
+    return;
+  }
+  // The wave that completes the session's C chunk masses draws the token.  The masses are
+  // published with device-coherent stores and read back with device-coherent loads, so the
+  // arrival counter needs no cache-wide fence.  The counter is left at zero for the next call.
+  int32_t arrived = 0;
+  if (lane == 0) {
+    publish(a.resid_mass + (int64_t)b * a.C + c, acc);
+    arrived = arrive(a.arrive_resid + b);
+  }
+  arrived = __builtin_amdgcn_readfirstlane(arrived);
+  if (arrived != a.C - 1) return;
+  if (lane == 0) __hip_atomic_store(a.arrive_resid + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  pick_for_session<BF16, ALIGNED, true>(a, b, job, lane);
 }
 
 // Inverse-CDF draw inside one chunk: target in [0, chunk mass) -> vocabulary index.
@@ -414,12 +436,7 @@ __device__ __forceinline__ int32_t pick_chunk(MassFn mass, int32_t C, float r, i
 // the position-n block.  Otherwise: all-accepted sessions, row gamma_b, weights P, r = word 2 of
 // the position-gamma_b block (Algorithm 2: "Sample x_{gamma+1} ~ P_{gamma+1}").
 template <bool BF16, bool ALIGNED, bool RESID>
-__global__ __launch_bounds__(256) void pick_token(const BatchView a) {
-  const int lane = threadIdx.x & 63;
-  const int32_t b = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (b >= a.B) return;
-  const Job job = RESID ? a.resid_job[b] : a.bonus_job[b];
-  if (job.lrow < 0) return;
+__device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, int lane) {
   const int64_t lrow = job.lrow;
   const int32_t n = (int32_t)(lrow - b - session_first_draft(a, b));   // position inside the session
   const float2 st = make_float2(job.M2, job.Z);
@@ -437,7 +454,7 @@ __global__ __launch_bounds__(256) void pick_token(const BatchView a) {
   bool from_p = !RESID;
   if constexpr (RESID) {
     const float* rm = a.resid_mass + (int64_t)b * a.C;
-    const int32_t c = pick_chunk([&](int32_t cc) { return rm[cc]; }, a.C, r, lane, &target, &total);
+    const int32_t c = pick_chunk([&](int32_t cc) { return observe(rm + cc); }, a.C, r, lane, &target, &total);
     if (c >= 0) token = pick_in_chunk(LogitWeights<BF16, ALIGNED, true>{lp, qp, a.V, c1, st.x, invZ}, c, target, lane);
     if (token < 0) from_p = true;   // residual mass rounded to zero: draw from P_n instead
   }
@@ -452,6 +469,18 @@ __global__ __launch_bounds__(256) void pick_token(const BatchView a) {
       if (token < 0) a.status[b] |= 8;
     }
   }
+}
+
+// Token draw as a launch of its own, one wave per session: the bonus token of all-accepted
+// sessions (RESID = false) or the redrawn token of rejected ones after resid_mass (RESID = true).
+template <bool BF16, bool ALIGNED, bool RESID>
+__global__ __launch_bounds__(256) void pick_token(const BatchView a) {
+  const int lane = threadIdx.x & 63;
+  const int32_t b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (b >= a.B) return;
+  const Job job = RESID ? a.resid_job[b] : a.bonus_job[b];
+  if (job.lrow < 0) return;
+  pick_for_session<BF16, ALIGNED, RESID>(a, b, job, lane);
 }
 
 }  // namespace dssd
