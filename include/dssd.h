@@ -135,6 +135,19 @@ dssd_status dssd_residual_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_ou
  * position-gamma_b block.  Other sessions are untouched. */
 dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
 
+/* The whole step in one call, as in Algorithm 1 where the edge does all of it: equivalent to
+ * dssd_verify_batch, dssd_residual_sample, dssd_bonus_sample in a row on the same stream, with
+ * bit-identical outputs.  Batches with uniform gamma (draft_offsets == NULL) whose grid is small
+ * (at most the limit set by dssd_set_fused_limit workgroups, default 512) and whose rows are
+ * short (V * (logit bytes + 4) <= 384 KiB) run as ONE kernel launch, which is what matters when
+ * a step is bound by launch latency rather than bandwidth; all others run as the three calls.
+ * Needs the full Q rows (draft_probs). */
+dssd_status dssd_step_fused(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
+/* Largest grid (workgroups = B * ceil((gamma+1) * chunks_per_row / 4)) that dssd_step_fused runs
+ * as a single launch; 0 disables the single-launch path; a negative value sets the limit to its
+ * magnitude and lifts the row-length rule (for tests and measurements). */
+dssd_status dssd_set_fused_limit(dssd_ctx *ctx, int64_t max_blocks);
+
 /* Edge side, Algorithm 2 "Downlink Transmission": after dssd_verify_batch, for every session
  * with rejected = 1 write the distribution at the rejected position, P_n(v) for v in [0, V), into
  * p_rows[b*V + v] as b_prob-bit values: p_dtype = DSSD_F32 (b_prob = 32) or DSSD_F16 (b_prob = 16,
@@ -170,15 +183,16 @@ dssd_status dssd_residual_sample_from_p(dssd_ctx *ctx, const dssd_device_batch *
 
 const char *dssd_status_str(dssd_status s);
 
-/* Kernel timing (measurement aid, not on the hot path).  While enabled, every kernel launch is
- * bracketed by HIP events on the launch stream.  Kernel ids: 0 row softmax statistics,
+/* Kernel timing (measurement aid, not on the hot path).  Bit k of kernel_mask brackets every
+ * launch of kernel k with HIP events on the launch stream (0 = off).  Each bracket costs a few
+ * microseconds of queue time, so time only the kernels a measurement needs.  Kernel ids: 0 row softmax statistics,
  * 1 accept / first-reject, 2 residual chunk masses (for small batches also the pick, in one
  * launch), 3 residual pick, 4 bonus pick, 5 export of P rows, 6 and 7 chunk masses and pick of
- * the device-side redraw. */
+ * the device-side redraw, 8 the single-launch step of dssd_step_fused. */
 enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
        DSSD_K_BONUS_PICK = 4, DSSD_K_EXPORT_P = 5, DSSD_K_DEVICE_MASS = 6, DSSD_K_DEVICE_PICK = 7,
-       DSSD_K_COUNT = 8 };
-dssd_status dssd_profile_enable(dssd_ctx *ctx, int enable);
+       DSSD_K_FUSED_STEP = 8, DSSD_K_COUNT = 9 };
+dssd_status dssd_profile_enable(dssd_ctx *ctx, uint32_t kernel_mask);
 /* Synchronises the recorded events, returns the summed duration (ms) and number of launches
  * of one kernel since the last reset. */
 dssd_status dssd_profile_read(dssd_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);

@@ -13,12 +13,12 @@ DSSD_F32, DSSD_BF16, DSSD_F16 = 0, 1, 2
 DSSD_OK, DSSD_EINVAL, DSSD_EALIGN, DSSD_ENOMEM, DSSD_EHIP, DSSD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 SESSION_BAD_TOKEN, SESSION_ZERO_RESIDUAL, SESSION_BAD_OFFSETS, SESSION_BAD_ROW = 1, 2, 4, 8
 K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
-K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_COUNT = 5, 6, 7, 8
+K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_COUNT = 5, 6, 7, 8, 9
 
 # every symbol include/dssd.h declares
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
-           "dssd_residual_sample_from_p", "dssd_status_str", "dssd_profile_enable",
+           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_status_str", "dssd_profile_enable",
            "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name")
 
 
@@ -69,7 +69,9 @@ def load():
     L.dssd_create.restype = C.c_int
     L.dssd_destroy.argtypes = [P]
     L.dssd_destroy.restype = None
-    for name in ("dssd_verify_batch", "dssd_residual_sample", "dssd_bonus_sample"):
+    L.dssd_set_fused_limit.argtypes = [P, C.c_int64]
+    L.dssd_set_fused_limit.restype = C.c_int
+    for name in ("dssd_verify_batch", "dssd_residual_sample", "dssd_bonus_sample", "dssd_step_fused"):
         f = getattr(L, name)
         f.argtypes = [P, C.POINTER(dssd_batch), C.POINTER(dssd_out), P]
         f.restype = C.c_int
@@ -81,7 +83,7 @@ def load():
     L.dssd_status_str.restype = C.c_char_p
     L.dssd_kernel_name.argtypes = [C.c_int]
     L.dssd_kernel_name.restype = C.c_char_p
-    L.dssd_profile_enable.argtypes = [P, C.c_int]
+    L.dssd_profile_enable.argtypes = [P, C.c_uint32]
     L.dssd_profile_enable.restype = C.c_int
     L.dssd_profile_reset.argtypes = [P]
     L.dssd_profile_reset.restype = C.c_int
@@ -135,6 +137,14 @@ def dssd_bonus_sample(ctx, batch, out, stream=0, check=True):
     return _call("dssd_bonus_sample", ctx, batch, out, stream, check)
 
 
+def dssd_step_fused(ctx, batch, out, stream=0, check=True):
+    return _call("dssd_step_fused", ctx, batch, out, stream, check)
+
+
+def dssd_set_fused_limit(ctx, max_blocks):
+    return load().dssd_set_fused_limit(ctx, int(max_blocks))
+
+
 def dssd_export_p_rows(ctx, batch, p_rows_ptr, p_dtype, stream=0, check=True):
     rc = load().dssd_export_p_rows(ctx, C.byref(batch), C.c_void_p(p_rows_ptr), int(p_dtype), C.c_void_p(stream or 0))
     if check and rc != DSSD_OK:
@@ -150,7 +160,9 @@ def dssd_residual_sample_from_p(ctx, device_batch, stream=0, check=True):
 
 
 def dssd_profile_enable(ctx, enable=True):
-    return load().dssd_profile_enable(ctx, 1 if enable else 0)
+    """enable: True = every kernel, False = off, or an int bit mask (bit k = kernel k)."""
+    mask = (0xFFFFFFFF if enable else 0) if isinstance(enable, bool) else int(enable)
+    return load().dssd_profile_enable(ctx, mask)
 
 
 def dssd_profile_reset(ctx):
@@ -247,6 +259,9 @@ class Context:
     def stream(self):
         import torch
         return torch.cuda.current_stream(self.device).cuda_stream
+
+    def step_fused(self, batch, out):
+        dssd_step_fused(self.handle, batch, out, self.stream())
 
     def step(self, batch, out):
         s = self.stream()

@@ -7,6 +7,7 @@
 #include <new>
 #include <vector>
 
+#include "dssd_fused_kernels.hpp"
 #include "dssd_split_kernels.hpp"
 
 using namespace dssd;
@@ -23,7 +24,10 @@ struct dssd_ctx {
   Job* resid_job = nullptr;
   Job* bonus_job = nullptr;
   int32_t* arrive_resid = nullptr;
-  bool profiling = false;
+  int32_t* arrive_stats = nullptr;
+  uint32_t profile_mask = 0;         // bit k: time kernel k
+  bool fused_force = false;          // set by dssd_set_fused_limit with a negative limit: ignore the row-size rule
+  int64_t fused_max_blocks = 512;    // dssd_step_fused: largest grid that runs as one launch
   std::vector<hipEvent_t> ev_begin[DSSD_K_COUNT], ev_end[DSSD_K_COUNT];
   size_t ev_used[DSSD_K_COUNT] = {};
 };
@@ -40,7 +44,7 @@ extern "C" size_t dssd_workspace_bytes(int64_t max_rows, int32_t max_V, int32_t 
   const size_t rows = (size_t)max_rows;
   return align256(rows * C * sizeof(float2)) + align256(rows * sizeof(float2)) +
          align256(rows * C * sizeof(float)) + 2 * align256(rows * sizeof(Job)) +
-         align256(rows * sizeof(int32_t));
+         align256(2 * rows * sizeof(int32_t));
 }
 
 extern "C" const char* dssd_status_str(dssd_status s) {
@@ -58,7 +62,7 @@ extern "C" const char* dssd_status_str(dssd_status s) {
 extern "C" const char* dssd_kernel_name(int k) {
   static const char* names[DSSD_K_COUNT] = {"row_chunk_stats", "accept_scan", "resid_mass", "resid_pick",
                                             "bonus_pick", "export_p_rows", "device_resid_mass",
-                                            "device_resid_pick"};
+                                            "device_resid_pick", "fused_small_step"};
   return (k >= 0 && k < DSSD_K_COUNT) ? names[k] : "?";
 }
 
@@ -88,8 +92,9 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   c->resid_job = reinterpret_cast<Job*>(p);      p += align256(rows * sizeof(Job));
   c->bonus_job = reinterpret_cast<Job*>(p);      p += align256(rows * sizeof(Job));
   c->arrive_resid = reinterpret_cast<int32_t*>(p);
+  c->arrive_stats = c->arrive_resid + rows;
   // arrival counters start at zero; every kernel that uses them leaves them at zero
-  if (hipMemset(c->arrive_resid, 0, rows * sizeof(int32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+  if (hipMemset(c->arrive_resid, 0, 2 * rows * sizeof(int32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
     (void)hipFree(c->workspace);
     delete c;
     return DSSD_EHIP;
@@ -157,7 +162,7 @@ namespace {
 struct Timed {
   dssd_ctx* c; int k; hipStream_t s; hipEvent_t end = nullptr; bool failed = false;
   Timed(dssd_ctx* c_, int k_, hipStream_t s_) : c(c_), k(k_), s(s_) {
-    if (!c->profiling) return;
+    if (!((c->profile_mask >> k) & 1u)) return;
     if (c->ev_used[k] == c->ev_begin[k].size()) {
       hipEvent_t a, b;
       if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { failed = true; return; }
@@ -246,6 +251,45 @@ extern "C" dssd_status dssd_bonus_sample(dssd_ctx* c, const dssd_batch* b, dssd_
   return launch_status();
 }
 
+// The whole step in one call: what Algorithm 1 does at the edge (accept/reject, redraw on a
+// rejection, bonus token otherwise).  Small batches with uniform gamma run as a single launch;
+// everything else is the three calls in a row.
+extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
+  BatchView v;
+  const dssd_status st = check_and_view(c, b, o, &v);
+  if (st != DSSD_OK || b->B == 0) return st;
+  if (b->total_drafts > 0 && !b->draft_probs) return DSSD_EINVAL;
+  const int64_t groups = ((int64_t)(b->gamma + 1) * v.C + 3) / 4;
+  // One launch pays only while the lone workgroup that finishes a session can stream the
+  // rejected row (logits + Q) quickly: small grids and rows of a few hundred KiB.
+  const int64_t resid_row_bytes = (int64_t)b->V * ((b->logits_dtype == DSSD_BF16 ? 2 : 4) + 4);
+  const bool single = !b->draft_offsets && groups * b->B <= c->fused_max_blocks &&
+                      (c->fused_force || resid_row_bytes <= (384 << 10));
+  if (!single) {
+    dssd_status r = dssd_verify_batch(c, b, o, hip_stream);
+    if (r == DSSD_OK) r = dssd_residual_sample(c, b, o, hip_stream);
+    if (r == DSSD_OK) r = dssd_bonus_sample(c, b, o, hip_stream);
+    return r;
+  }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  {
+    Timed t(c, DSSD_K_FUSED_STEP, s);
+    const unsigned grid = (unsigned)(groups * b->B);
+    const int32_t g32 = (int32_t)groups;
+    if (bf16) { if (al) DSSD_LAUNCH((fused_small_step<true, true>), grid, s, v, g32, c->arrive_stats); else DSSD_LAUNCH((fused_small_step<true, false>), grid, s, v, g32, c->arrive_stats); }
+    else      { if (al) DSSD_LAUNCH((fused_small_step<false, true>), grid, s, v, g32, c->arrive_stats); else DSSD_LAUNCH((fused_small_step<false, false>), grid, s, v, g32, c->arrive_stats); }
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_set_fused_limit(dssd_ctx* c, int64_t max_blocks) {
+  if (!c) return DSSD_EINVAL;
+  c->fused_force = max_blocks < 0;
+  c->fused_max_blocks = max_blocks < 0 ? -max_blocks : max_blocks;
+  return DSSD_OK;
+}
+
 extern "C" dssd_status dssd_export_p_rows(dssd_ctx* c, const dssd_batch* b, void* p_rows, int32_t p_dtype,
                                           void* hip_stream) {
   BatchView v;
@@ -314,9 +358,9 @@ extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_devic
   return launch_status();
 }
 
-extern "C" dssd_status dssd_profile_enable(dssd_ctx* c, int enable) {
+extern "C" dssd_status dssd_profile_enable(dssd_ctx* c, uint32_t kernel_mask) {
   if (!c) return DSSD_EINVAL;
-  c->profiling = enable != 0;
+  c->profile_mask = kernel_mask;
   return DSSD_OK;
 }
 

@@ -157,6 +157,15 @@ __device__ __forceinline__ void publish(float* p, float v) {
 __device__ __forceinline__ float observe(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void publish2(float2* p, float2 v) {
+  const uint64_t bits = (uint64_t)as_u32(v.x) | ((uint64_t)as_u32(v.y) << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 observe2(const float2* p) {
+  const uint64_t bits =
+      __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(as_float((uint32_t)bits), as_float((uint32_t)(bits >> 32)));
+}
 __device__ __forceinline__ int32_t arrive(int32_t* counter) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's stores have completed
   return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

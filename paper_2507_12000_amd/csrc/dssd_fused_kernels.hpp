@@ -1,0 +1,61 @@
+// Single-launch verification step for small batches with uniform gamma (the paper's own
+// scenario is one session per device; Algorithm 1 with everything at the edge).  When a batch
+// has only a few thousand chunks the step is bound by launch latency, not by HBM, so the five
+// kernels of the streaming path are chained inside one launch:
+//
+//   every workgroup   : softmax statistics of up to four chunks of its session's rows, published
+//                       with device-coherent stores; then it bumps the session's arrival counter;
+//   the workgroup that arrives last for a session goes on alone (no workgroup ever waits):
+//                       merges the rows, runs the accept / first-reject scan, and either
+//                       - computes the residual chunk masses of the rejected row with its four
+//                         waves and draws the token, or
+//                       - draws the bonus token from the chunk statistics.
+// Results are bit-identical to the three-call path: the same device functions in the same order.
+#pragma once
+#include "dssd_kernels.hpp"
+
+namespace dssd {
+
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32_t groups, int32_t* arrive_stats) {
+  __shared__ int32_t sh_last;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int32_t b = blockIdx.x / groups;
+  const int32_t j = blockIdx.x - b * groups;
+  const int32_t g = a.gamma;                         // uniform gamma only
+  const int64_t lrow0 = (int64_t)b * (g + 1);
+  const int32_t ntask = (g + 1) * a.C;               // chunk tasks of this session
+  const int32_t t = j * 4 + wave;
+  if (t < ntask) {
+    const int32_t i = t / a.C, c = t - i * a.C;
+    const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
+    const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, lrow0 + i), c, a.V, c1, lane);
+    if (lane == 0) {
+      publish2(a.chunk_stats + (lrow0 + i) * a.C + c, st);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the store has completed
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0)
+    sh_last = __hip_atomic_fetch_add(arrive_stats + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == groups - 1;
+  __syncthreads();
+  if (!sh_last) return;
+  if (threadIdx.x == 0) __hip_atomic_store(arrive_stats + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // ---- the last workgroup of session b carries the session to its token
+  Job job;
+  const int32_t kind = accept_session<BF16>(a, b, &job);
+  if (kind == 1) {
+    for (int32_t c = wave; c < a.C; c += 4) {
+      const float m = resid_chunk_mass<BF16, ALIGNED>(a, b, job, c, lane);
+      if (lane == 0) publish(a.resid_mass + (int64_t)b * a.C + c, m);
+    }
+    if (lane == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (wave == 0) pick_for_session<BF16, ALIGNED, true>(a, b, job, lane);
+  } else if (kind == 2) {
+    if (wave == 0) pick_for_session<BF16, ALIGNED, false>(a, b, job, lane);
+  }
+}
+
+}  // namespace dssd

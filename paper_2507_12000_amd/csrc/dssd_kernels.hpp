@@ -70,22 +70,14 @@ template <bool BF16> __device__ __forceinline__ const char* logits_row(const Bat
 // Softmax statistics, one wave per chunk.  Step "LLM gets the gamma+1 distributions" of the
 // verification process: P(v) = 2^(z_v*c1 - M2)/Z.  This kernel reads every logit exactly once.
 // ---------------------------------------------------------------------------------------
+// (m2_c, s_c) of chunk c of the row at `src`, computed by one wave; every lane gets the result.
 template <bool BF16, bool ALIGNED>
-__global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
+__device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int32_t V, float c1, int lane) {
   constexpr int E = Elems<BF16>::per_vec;
-  const int lane = threadIdx.x & 63;
-  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
-  if (task >= a.R_L * a.C) return;
-  const int64_t row = task / a.C;
-  const int32_t c = (int32_t)(task - row * a.C);
-  float c1 = kLog2e;
-  if (a.inv_temp) c1 *= a.inv_temp[session_of_row(a, row)];
-  const char* src = logits_row<BF16>(a, row);
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
-
   float z[kUnroll][E];
 #pragma unroll
-  for (int k = 0; k < kUnroll; ++k) load_logits<BF16, ALIGNED>(src, v0 + k * kWave, a.V, z[k]);
+  for (int k = 0; k < kUnroll; ++k) load_logits<BF16, ALIGNED>(src, v0 + k * kWave, V, z[k]);
 
   float mx = neg_inf();
 #pragma unroll
@@ -104,7 +96,20 @@ __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
       for (int e = 0; e < E; ++e) acc[e & 3] += fast_exp2(fmaf(z[k][e], c1, -m2));
     s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
   }
-  if (lane == 0) a.chunk_stats[task] = make_float2(m2, s);
+  return make_float2(m2, s);
+}
+
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
+  if (task >= a.R_L * a.C) return;
+  const int64_t row = task / a.C;
+  const int32_t c = (int32_t)(task - row * a.C);
+  float c1 = kLog2e;
+  if (a.inv_temp) c1 *= a.inv_temp[session_of_row(a, row)];
+  const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, row), c, a.V, c1, lane);
+  if (lane == 0) a.chunk_stats[task] = st;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -117,23 +122,29 @@ __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
 __device__ __forceinline__ float2 merge_row_wave(const float2* cs, int32_t C, int lane, float2 first) {
   float M2 = wave_max(lane < C ? first.x : neg_inf());
   for (int32_t base = kWave; base < C; base += kWave)
-    M2 = fmaxf(M2, wave_max(base + lane < C ? cs[base + lane].x : neg_inf()));
+    M2 = fmaxf(M2, wave_max(base + lane < C ? observe2(cs + base + lane).x : neg_inf()));
   if (!(M2 > neg_inf())) return make_float2(M2, 0.f);
   float Z = wave_sum(lane < C ? first.y * fast_exp2(first.x - M2) : 0.f);
   for (int32_t base = kWave; base < C; base += kWave) {
     const int32_t c = base + lane;
-    Z += wave_sum(c < C ? cs[c].y * fast_exp2(cs[c].x - M2) : 0.f);
+    const float2 v = c < C ? observe2(cs + c) : make_float2(neg_inf(), 0.f);
+    Z += wave_sum(v.y * fast_exp2(v.x - M2));
   }
   return make_float2(M2, Z);
 }
 
 // One 256-thread workgroup per session.  The four waves merge the session's rows (four rows
 // per wave in flight at a time); wave 0 then takes lane i = draft position i.
+// Returns (to every thread of the workgroup) what the session has to draw next: kind 1 = redraw
+// from the residual at job.lrow, kind 2 = bonus token from job.lrow, 0 = nothing (device-side
+// error).  Chunk pairs are read with device-coherent loads, so the caller may be the launch that
+// produced them.
 template <bool BF16>
-__global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
+__device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out) {
   __shared__ float2 row_st[kWave + 1];
+  __shared__ Job sh_job;
+  __shared__ int32_t sh_kind;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int32_t b = blockIdx.x;
   const int64_t off0 = session_first_draft(a, b);
   const int64_t off1 = a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma;
   int32_t bad = 0;
@@ -157,7 +168,7 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int32_t r = r0 + 4 * j;
-          first[j] = (r < nrows && lane < a.C) ? a.chunk_stats[(lrow0 + base + r) * a.C + lane]
+          first[j] = (r < nrows && lane < a.C) ? observe2(a.chunk_stats + (lrow0 + base + r) * a.C + lane)
                                                : make_float2(neg_inf(), 0.f);
         }
 #pragma unroll
@@ -234,7 +245,19 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
     a.resid_job[b] = (!bad && first_reject < g) ? job : none;
     a.bonus_job[b] = (!bad && first_reject == g) ? job : none;
     if (a.status) a.status[b] = bad;
+    sh_job = job;
+    sh_kind = bad ? 0 : (first_reject < g ? 1 : 2);
   }
+  __syncthreads();
+  *job_out = sh_job;
+  return sh_kind;
+}
+
+// One 256-thread workgroup per session.
+template <bool BF16>
+__global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
+  Job job;
+  accept_session<BF16>(a, blockIdx.x, &job);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -284,22 +307,15 @@ __device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, 
 // wave of a session to finish also draws the token, which saves the second launch -- worth it
 // for small batches only (measured: the per-wave arrival costs more than a launch once there
 // are more than a few thousand chunk waves).
-template <bool BF16, bool ALIGNED, bool FUSE_PICK>
-__global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t groups) {
+template <bool BF16, bool ALIGNED>
+__device__ __forceinline__ float resid_chunk_mass(const BatchView& a, int32_t b, const Job& job, int32_t c,
+                                                  int lane) {
   constexpr int E = Elems<BF16>::per_vec;
-  const int lane = threadIdx.x & 63;
-  const int64_t blk = blockIdx.x;   // plain order: measured faster here than the XCD-contiguous map
-  const int32_t b = (int32_t)(blk / groups);
-  const int32_t c = (int32_t)(blk - (int64_t)b * groups) * 4 + (threadIdx.x >> 6);
-  if (c >= a.C) return;
-  const Job job = a.resid_job[b];
-  if (job.lrow < 0) return;
-  const int64_t lrow = job.lrow;
   const float2 st = make_float2(job.M2, job.Z);
   const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
   const float invZ = 1.f / st.y;
-  const char* lp = logits_row<BF16>(a, lrow);
-  const float* qp = a.draft_probs + (lrow - b) * (int64_t)a.V;   // draft row = logits row - session
+  const char* lp = logits_row<BF16>(a, job.lrow);
+  const float* qp = a.draft_probs + (job.lrow - b) * (int64_t)a.V;   // draft row = logits row - session
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
   // Two half-chunks of 4 groups each (12 loads in flight per lane): measured faster than all 8
   // groups at once, which costs occupancy (three input streams here, not one).
@@ -318,7 +334,19 @@ __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t gro
       for (int e = 0; e < E; ++e)
         acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z[k][e], c1, -st.x)), invZ, -q[k][e]));
   }
-  acc = wave_sum(acc);
+  return wave_sum(acc);
+}
+
+template <bool BF16, bool ALIGNED, bool FUSE_PICK>
+__global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t groups) {
+  const int lane = threadIdx.x & 63;
+  const int64_t blk = blockIdx.x;   // plain order: measured faster here than the XCD-contiguous map
+  const int32_t b = (int32_t)(blk / groups);
+  const int32_t c = (int32_t)(blk - (int64_t)b * groups) * 4 + (threadIdx.x >> 6);
+  if (c >= a.C) return;
+  const Job job = a.resid_job[b];
+  if (job.lrow < 0) return;
+  const float acc = resid_chunk_mass<BF16, ALIGNED>(a, b, job, c, lane);
   if constexpr (!FUSE_PICK) {
     if (lane == 0) a.resid_mass[(int64_t)b * a.C + c] = acc;
     return;
@@ -448,7 +476,7 @@ __device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, 
   const float r = u01(rnd.w[RESID ? 1 : 2]);
 
   const float2* cs = a.chunk_stats + lrow * a.C;
-  auto p_mass = [&](int32_t c) { return cs[c].y * fast_exp2(cs[c].x - st.x); };
+  auto p_mass = [&](int32_t c) { const float2 v = observe2(cs + c); return v.y * fast_exp2(v.x - st.x); };
   float target = 0.f, total = 0.f;
   int32_t token = -1;
   bool from_p = !RESID;

@@ -189,3 +189,54 @@ def test_empty_batch_gamma_zero_and_errors(ctx):
     batch = D.make_batch(inputs, seed=1); batch.logits_dtype = 9
     assert D.dssd_bonus_sample(ctx.handle, batch, out, 0, check=False) == D.DSSD_EINVAL
     torch.cuda.synchronize()
+
+
+FUSED_CASES = [w for w in SMALL if w.gamma_range is None] + [
+    synth.WORKLOADS[0], synth.WORKLOADS[1],
+    synth.Workload("fused_temp_bf16", B=48, V=50000, gamma=6, dtype="bf16", sigmas=(0.3, 1.5),
+                   temperature_range=(0.6, 1.4), frac_q_equals_p=0.1, frac_q_uniform=0.1),
+]
+
+
+@pytest.mark.parametrize("w", FUSED_CASES, ids=[w.name for w in FUSED_CASES])
+def test_fused_step_equals_three_calls(ctx, w):
+    """dssd_step_fused (one launch for these sizes) writes exactly what the three calls write,
+    on consecutive calls (its arrival counters must return to zero), and matches the oracle."""
+    inputs = synth.generate(w, seed=2, device=DEV)
+    D.dssd_set_fused_limit(ctx.handle, -(1 << 20))
+    try:
+        for step in (0, 1, 2):
+            ref = gpu_step(ctx, inputs, 31, step)
+            batch = D.make_batch(inputs, seed=31, step=step)
+            t, out = D.alloc_out(inputs, DEV)
+            D.dssd_profile_reset(ctx.handle)
+            D.dssd_profile_enable(ctx.handle, True)
+            ctx.step_fused(batch, out)
+            torch.cuda.synchronize()
+            D.dssd_profile_enable(ctx.handle, False)
+            assert D.dssd_profile_read(ctx.handle, D.K_FUSED_STEP)[1] == 1      # it really was one launch
+            assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)[1] == 0
+            got = {k: v.cpu().numpy() for k, v in t.items()}
+            for k in ref:
+                assert (ref[k] == got[k]).all(), (k, step)
+        h = parity.to_numpy_inputs(inputs)
+        orc = parity.run_oracle(h, 31, 2, workers=8)
+        parity.compare(h, got, orc, P_RTOL[w.dtype], seed=31, step=2)
+    finally:
+        D.dssd_set_fused_limit(ctx.handle, 512)
+
+
+def test_fused_step_falls_back_for_ragged_and_large(ctx):
+    w = synth.Workload("fused_ragged", B=21, V=7000, gamma=0, dtype="bf16", gamma_range=(1, 5))
+    inputs = synth.generate(w, seed=3, device=DEV)
+    ref = gpu_step(ctx, inputs, 4, 0)
+    t, out = D.alloc_out(inputs, DEV)
+    D.dssd_profile_reset(ctx.handle)
+    D.dssd_profile_enable(ctx.handle, True)
+    ctx.step_fused(D.make_batch(inputs, seed=4, step=0), out)
+    torch.cuda.synchronize()
+    D.dssd_profile_enable(ctx.handle, False)
+    assert D.dssd_profile_read(ctx.handle, D.K_FUSED_STEP)[1] == 0
+    assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)[1] == 1
+    for k in ref:
+        assert (ref[k] == t[k].cpu().numpy()).all(), k
