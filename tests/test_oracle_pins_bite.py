@@ -15,8 +15,18 @@ MUTATIONS = {
     "residual_sign": ("const double d = P[v] - (double)Q[v];", "const double d = (double)Q[v] - P[v];"),
     "residual_uses_accept_word": ("const double r2 = dssd_oracle_u01(words[1]);",
                                   "const double r2 = dssd_oracle_u01(words[0]);"),
-    "bonus_uses_residual_word": ("dssd_oracle_u01(words[2]), &res->cdf_margin);",
-                                 "dssd_oracle_u01(words[1]), &res->cdf_margin);"),
+    "bonus_uses_residual_word": ("dssd_oracle_u01(words[2]), &res->cdf_margin);\n  }\n}",
+                                 "dssd_oracle_u01(words[1]), &res->cdf_margin);\n  }\n}"),
+    "edge_bonus_uses_residual_word": ("dssd_oracle_u01(words[2]), &res->cdf_margin);\n      return;",
+                                      "dssd_oracle_u01(words[1]), &res->cdf_margin);\n      return;"),
+    "device_uses_accept_word": ("const double r = dssd_oracle_u01(words[1]);\n  if (resid_mass)",
+                                "const double r = dssd_oracle_u01(words[0]);\n  if (resid_mass)"),
+    "half_truncates": ("if (rem > 0x1000u || (rem == 0x1000u && (half & 1u))) ++half;", ";"),
+    "half_ties_away": ("if (rem > 0x1000u || (rem == 0x1000u && (half & 1u))) ++half;",
+                       "if (rem >= 0x1000u) ++half;"),
+    "edge_exports_wrong_row": ("      dssd_oracle_quantize_p_row(P.data(), V, p_dtype, p_row_out);\n      return;",
+                               "      if (i > 0) dssd_oracle_softmax_row((const char*)logits, dtype, V, inv_temperature, P.data(), &m, &Z);\n"
+                               "      dssd_oracle_quantize_p_row(P.data(), V, p_dtype, p_row_out);\n      return;"),
     "cdf_not_strict": ("if (upto > t) {", "if (upto >= t) {"),
     "temperature_dropped": ("const double e = std::exp(logit_at(logits_row, dtype, v) * inv_temperature - m);",
                             "const double e = std::exp(logit_at(logits_row, dtype, v) - m);"),
@@ -26,11 +36,12 @@ MUTATIONS = {
     "u01_uses_low_bits": ("return (double)(w >> 8) * (1.0 / 16777216.0);",
                           "return (double)(w & 0xFFFFFF) * (1.0 / 16777216.0);"),
     "bonus_row_off_by_one": ("if (i == gamma) break;", "if (i == gamma - 1 && gamma > 1) break;"),
-    "stops_one_late": ("res->n = i;\n      res->rejected = 1;", "res->n = i + 1 < gamma ? i + 1 : i;\n      res->rejected = 1;"),
+    "stops_one_late": ("open = false;  // Flag = 0\n      res->n = i;",
+                       "open = false;  // Flag = 0\n      res->n = i + 1 < gamma ? i + 1 : i;"),
 }
 
 PIN_TESTS = ["tests/test_oracle_philox.py", "tests/test_oracle_softmax.py", "tests/test_oracle_accept_cdf.py",
-             "tests/test_oracle_law.py"]
+             "tests/test_oracle_law.py", "tests/test_oracle_split.py"]
 
 
 def _run_pins(lib):
