@@ -7,9 +7,10 @@
 //                     c1 = log2(e)/T.  One exp per element, no cross-wave traffic.
 //   accept_scan     : per session (one workgroup), merges the chunk pairs into row (M2, Z), gathers
 //                     p_i(x_i) and q_i(x_i), draws r_i, finds the first rejected draft with a ballot.
-//   resid_mass      : per chunk of the rejected row, the mass of max(0, P - Q).
-//   resid_pick / bonus_pick : scan the chunk masses, then re-read the one chunk that holds
-//                     r * total and locate the token by a wave prefix sum.
+//   resid_mass      : per chunk of the rejected row, the mass of max(0, P - Q); for small
+//                     batches the last wave of a session also draws the token.
+//   pick_token      : scan the chunk masses, then re-read the one chunk that holds r * total
+//                     and locate the token by a wave prefix sum (residual or bonus draw).
 #pragma once
 #include "dssd_device.hpp"
 
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Accept / reject and first-reject scan, one wave per session, lane i = draft position i.
+// Accept / reject and first-reject scan, one workgroup per session.
 // Algorithm 2, "Verification Process" loop: accept x_i iff r_i < min(1, p_i(x_i)/q_i(x_i)),
 // evaluated as r_i*q < p; stop at the first failure.
 // ---------------------------------------------------------------------------------------

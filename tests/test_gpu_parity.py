@@ -240,3 +240,75 @@ def test_fused_step_falls_back_for_ragged_and_large(ctx):
     assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)[1] == 1
     for k in ref:
         assert (ref[k] == t[k].cpu().numpy()).all(), k
+
+
+EXTREME = [
+    # the largest vocabulary the module's context takes; exactly 64 chunks of bf16
+    synth.Workload("bf16_V262144", B=3, V=262144, gamma=2, dtype="bf16", sigmas=(1.0,)),
+    # gamma = 64: 65 rows per session, two passes of the 64-lane accept scan
+    synth.Workload("f32_gamma64", B=3, V=1000, gamma=64, dtype="f32", sigmas=(0.05,)),
+    # many short sessions
+    synth.Workload("f32_B2000", B=2000, V=512, gamma=2, dtype="f32", sigmas=(1.0,)),
+]
+
+
+@pytest.mark.parametrize("w", EXTREME, ids=[w.name for w in EXTREME])
+def test_extreme_shapes(ctx, w):
+    check(ctx, w, seed=99, step=5, workers=16)
+
+
+def test_misaligned_base_pointers_take_the_scalar_path(ctx):
+    """V is a multiple of 8 but the buffers start 4 bytes into a 16-byte line."""
+    w = synth.Workload("shifted", B=6, V=8192 + 64, gamma=3, dtype="f32", sigmas=(1.0,))
+    inputs = synth.generate(w, seed=8, device=DEV)
+    lg = torch.empty(inputs["logits"].numel() + 1, device=DEV, dtype=torch.float32)[1:].view_as(inputs["logits"])
+    lg.copy_(inputs["logits"])
+    dq = torch.empty(inputs["draft_probs"].numel() + 1, device=DEV, dtype=torch.float32)[1:].view_as(inputs["draft_probs"])
+    dq.copy_(inputs["draft_probs"])
+    assert lg.data_ptr() % 16 == 4 and dq.data_ptr() % 16 == 4
+    shifted = dict(inputs, logits=lg, draft_probs=dq)
+    a = gpu_step(ctx, inputs, 3, 1)
+    b = gpu_step(ctx, shifted, 3, 1)
+    for k in ("accepted_len", "rejected", "out_token", "status", "q_tok"):
+        assert (a[k] == b[k]).all(), k
+    np.testing.assert_allclose(a["p_tok"], b["p_tok"], rtol=1e-6)
+    h = parity.to_numpy_inputs(shifted)
+    parity.compare(h, b, parity.run_oracle(h, 3, 1, workers=4), 1e-5, seed=3, step=1)
+
+
+def test_twenty_runs_are_bit_identical(ctx):
+    w = synth.Workload("repeat", B=128, V=50000, gamma=5, dtype="bf16", sigmas=(1.0,))
+    inputs = synth.generate(w, seed=12, device=DEV)
+    first = gpu_step(ctx, inputs, 1, 1)
+    for _ in range(20):
+        again = gpu_step(ctx, inputs, 1, 1)
+        for k in first:
+            assert (first[k] == again[k]).all(), k
+
+
+def test_step_inside_a_hip_graph(ctx):
+    """The three calls allocate nothing and never synchronise, so a caller can capture them in a
+    graph.  Replays (with eager work and synchronisations in between) reproduce the eager result."""
+    w = synth.Workload("graph", B=32, V=40000, gamma=4, dtype="bf16", sigmas=(1.0,))
+    inputs = synth.generate(w, seed=13, device=DEV)
+    eager = gpu_step(ctx, inputs, 21, 4)
+    batch = D.make_batch(inputs, seed=21, step=4)
+    t, out = D.alloc_out(inputs, DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        ctx.step(batch, out)                      # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            ctx.step(batch, out)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for v in t.values():
+            v.fill_(-3)                           # eager work between replays; also proves the replay writes
+        other = gpu_step(ctx, inputs, 5, rep)     # the context's workspace is overwritten in between
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ("accepted_len", "rejected", "out_token", "p_tok", "row_stats", "status"):
+            assert (t[k].cpu().numpy() == eager[k]).all(), (k, rep)
+        assert other["out_token"].shape == eager["out_token"].shape
