@@ -15,6 +15,9 @@ Recipe (one generator for every workload):
   * draft token x ~ Q (torch.multinomial);
   * optional per-session temperature T ~ U[T_lo, T_hi], applied to both models;
   * optional ragged batch: gamma_b ~ U{g_lo..g_hi}, rows packed with prefix-sum offsets;
+  * optional top-k truncation (the paper's experiments sample with k = 10): the target logits
+    outside each row's k largest are stored as -inf and each draft row keeps only its own k
+    largest entries, renormalised (the draft is drawn from the full target row first);
   * optional session classes: a fraction with Q == P (Q = softmax of the stored target
     logits, so every draft is accepted up to rounding) and a fraction with Q uniform.
 """
@@ -37,6 +40,7 @@ class Workload:
     gamma_range: Optional[Tuple[int, int]] = None
     frac_q_equals_p: float = 0.0
     frac_q_uniform: float = 0.0
+    top_k: int = 0                               # > 0: both models truncated to their own top-k tokens
 
 
 # The five workloads of the benchmark definition, by index.
@@ -113,6 +117,9 @@ def generate(w: Workload, seed: int = 0, device="cpu", sessions_per_chunk: int =
         z = 2.0 * torch.randn((l1 - l0, V), generator=g, device=dev, dtype=torch.float32) + bias
         logits[l0:l1] = z.to(store)
         if q1 == q0:
+            if w.top_k > 0:
+                kth = torch.topk(z, min(w.top_k, V), dim=1).values[:, -1:]
+                logits[l0:l1] = torch.where(z >= kth, z, torch.full_like(z, float("-inf"))).to(store)
             continue
         # session of every draft row in the chunk, and the logits row it is paired with
         sess = torch.repeat_interleave(torch.arange(b0, b1, device=dev), gammas[b0:b1])
@@ -125,11 +132,18 @@ def generate(w: Workload, seed: int = 0, device="cpu", sessions_per_chunk: int =
         y = zs + sig[:, None] * noise
         if inv_temperature is not None:
             y = y * inv_temperature[sess][:, None]
+        if w.top_k > 0:
+            kth = torch.topk(y, min(w.top_k, V), dim=1).values[:, -1:]
+            y = torch.where(y >= kth, y, torch.full_like(y, float("-inf")))
         Q = torch.softmax(y, dim=1)
         Q[cls == 2] = 1.0 / V
         draft_probs[q0:q1] = Q
         draft_tokens[q0:q1] = torch.multinomial(Q, 1, generator=g).squeeze(1).to(torch.int32)
         del z, zs, noise, y, Q
+        if w.top_k > 0:
+            zf = logits[l0:l1].to(torch.float32)
+            kth = torch.topk(zf, min(w.top_k, V), dim=1).values[:, -1:]
+            logits[l0:l1] = torch.where(zf >= kth, zf, torch.full_like(zf, float("-inf"))).to(store)
 
     uniform = w.gamma_range is None
     return dict(

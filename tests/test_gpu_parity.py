@@ -61,6 +61,11 @@ SMALL = [
     synth.Workload("f32_many_chunks", B=3, V=2048 * 70 + 12, gamma=2, dtype="f32", sigmas=(2.0,)),
     # gamma above one wave of positions
     synth.Workload("f32_long_gamma", B=2, V=300, gamma=70, dtype="f32", sigmas=(0.1,)),
+    # top-k truncated supports (the paper's experiments sample with k = 10): -inf logits and
+    # zero draft probabilities everywhere else, whole chunks without any mass
+    synth.Workload("bf16_topk10", B=40, V=20000, gamma=4, dtype="bf16", sigmas=(1.0,), top_k=10),
+    synth.Workload("f32_topk10_ragged", B=31, V=9000, gamma=0, dtype="f32", gamma_range=(1, 8), sigmas=(0.5, 2.0),
+                   top_k=10, temperature_range=(0.7, 1.3)),
 ]
 
 

@@ -338,3 +338,38 @@ def test_one_hot_draft_on_unlikely_token_and_bad_tokens():
     assert len(seen) == V - 1
     out = O.verify_batch(z, O.F32, Q, np.array([5, V], np.int32), V, gamma=gamma, seed=1, step=0)
     assert out["res"][0]["status"] & 1 and out["res"][0]["token"] == -1
+
+
+def test_top_k_truncated_supports():
+    """The paper's experiments sample with top-k (k = 10): both distributions live on k tokens.
+    Emitted tokens stay inside the target's support, a draft outside it is always rejected, and
+    the redraw never lands where the residual is zero."""
+    import torch
+    from paper_2507_12000_amd import synth
+    w = synth.Workload("topk", B=300, V=2000, gamma=4, dtype="bf16", sigmas=(1.0,), top_k=10)
+    d = synth.generate(w, seed=5, device="cpu")
+    stored = d["logits"].view(torch.int16).numpy().view(np.uint16)
+    Q = d["draft_probs"].numpy(); tok = d["draft_tokens"].numpy()
+    out = O.verify_batch(stored, O.BF16, Q, tok, w.V, gamma=w.gamma, seed=6, step=0)
+    res = out["res"]
+    assert (res["status"] == 0).all() and 0.2 < res["rejected"].mean() < 0.999
+    support = np.isfinite((stored.astype(np.uint32) << 16).view(np.float32)) & \
+        ((stored.astype(np.uint32) << 16).view(np.float32) > -1e30)
+    # (ties at the k-th value after bf16 rounding may keep a few more than k)
+    assert (support.sum(1) >= 10).all() and (support.sum(1) <= 14).all() and ((Q > 0).sum(1) == 10).all()
+    g = w.gamma
+    for b in range(w.B):
+        n = res["n"][b]
+        lrow = b * (g + 1) + n
+        assert support[lrow, res["token"][b]]                      # emitted token has target mass
+        for i in range(min(n + 1, g)):
+            x = tok[b * g + i]
+            in_support = support[b * (g + 1) + i, x]
+            if i < n:
+                assert in_support                                   # accepted drafts are in the target's top-k
+            elif not in_support:
+                assert out["p_tok"][b * g + i] == 0.0              # p = 0: rejected whatever r is
+        if res["rejected"][b]:
+            assert out["p_tok"][b * g + n] < Q[b * g + n, tok[b * g + n]] or out["p_tok"][b * g + n] == 0.0
+            P = O.softmax_row(stored[lrow], O.BF16)[0]
+            assert P[res["token"][b]] > Q[b * g + n, res["token"][b]]
