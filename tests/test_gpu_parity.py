@@ -317,3 +317,22 @@ def test_step_inside_a_hip_graph(ctx):
         for k in ("accepted_len", "rejected", "out_token", "p_tok", "row_stats", "status"):
             assert (t[k].cpu().numpy() == eager[k]).all(), (k, rep)
         assert other["out_token"].shape == eager["out_token"].shape
+
+
+def test_non_finite_logits_are_flagged_not_followed(ctx):
+    """A NaN or +inf logit poisons its row's softmax: the session is reported (BAD_ROW) and
+    skipped by the samplers; its neighbours are untouched."""
+    w = synth.Workload("nonfinite", B=8, V=9000, gamma=3, dtype="f32", sigmas=(1.0,))
+    inputs = synth.generate(w, seed=4, device=DEV)
+    clean = gpu_step(ctx, inputs, 2, 2)
+    bad = dict(inputs, logits=inputs["logits"].clone())
+    g = w.gamma
+    bad["logits"][2 * (g + 1) + 1, 17] = float("nan")       # session 2, row 1
+    bad["logits"][5 * (g + 1) + g, 4000] = float("inf")     # session 5, bonus row
+    got = gpu_step(ctx, bad, 2, 2)
+    for b in (2, 5):
+        assert got["status"][b] & D.SESSION_BAD_ROW
+        assert (got["accepted_len"][b], got["rejected"][b], got["out_token"][b]) == (0, 1, -1)
+    keep = np.array([b not in (2, 5) for b in range(w.B)])
+    for k in ("accepted_len", "rejected", "out_token", "status"):
+        assert (got[k][keep] == clean[k][keep]).all(), k
