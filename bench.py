@@ -162,6 +162,11 @@ def main():
                     help="run the step through dssd_step_fused (one launch where the batch allows it)")
     ap.add_argument("--fused-limit", type=int, default=None,
                     help="largest grid (workgroups) dssd_step_fused runs as one launch (library default 4096)")
+    ap.add_argument("--top-k", type=int, default=0,
+                    help="truncate both models to their top-k tokens (the paper's experiments use k = 10) and "
+                         "run the step in sparse-support mode; 0 = the benchmark workload as defined")
+    ap.add_argument("--top-k-dense", action="store_true",
+                    help="with --top-k: keep the dense samplers (no DSSD_FLAG_SPARSE_SUPPORT)")
     ap.add_argument("--split", action="store_true",
                     help="also time the edge/device split path (q scalars up, fp16 P rows down)")
     ap.add_argument("--gpus", type=int, default=1)
@@ -199,10 +204,14 @@ def main():
                           "launches": 10, "GBps_read_plus_write": 4 * n / dt / 1e9}))
         return
     w = synth.WORKLOADS[args.config]
+    flags = 0
+    if args.top_k > 0:
+        w = synth.scaled(w, top_k=args.top_k, name=f"{w.name}_top{args.top_k}")
+        flags = 0 if args.top_k_dense else D.FLAG_SPARSE_SUPPORT
     inputs = synth.generate(w, seed=args.seed, device=dev)
     torch.cuda.synchronize()
     ctx = D.Context(dev, max_rows=inputs["R_L"], max_V=w.V)
-    batch = D.make_batch(inputs, seed=args.seed, step=0)
+    batch = D.make_batch(inputs, seed=args.seed, step=0, flags=flags)
     outs, out = D.alloc_out(inputs, dev, debug=False)
 
     step_fn = ctx.step_fused if args.fused else ctx.step
@@ -256,6 +265,9 @@ def main():
     chunk_elems = 4096 if s_L == 2 else 2048
     C = -(-w.V // chunk_elems)
     ab = algorithmic_bytes(inputs, rejected, 1.0 / C)
+    if flags & D.FLAG_SPARSE_SUPPORT:   # the samplers touch a few dozen entries per session, not rows
+        ab["total"] -= ab["residual"] + ab["bonus"]
+        ab["residual"] = ab["bonus"] = 0
     ms_per_step = 1e3 * elapsed / args.steps
     # dominant kernel: the row statistics, or the single fused launch when the step ran as one
     dom = D.kernel_name(dom_id)
@@ -275,6 +287,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "entry": "dssd_step_fused" if args.fused else
                    "dssd_verify_batch+dssd_residual_sample+dssd_bonus_sample", "B": w.B, "V": w.V, "logits_dtype": w.dtype,
+                   "top_k": args.top_k, "sparse_support": bool(flags & D.FLAG_SPARSE_SUPPORT),
                    "logits_rows": inputs["R_L"], "draft_positions": inputs["R_Q"],
                    "rejected_sessions": int(rejected.sum())},
         "vocab_rows_per_sec": inputs["R_L"] * args.steps / elapsed,

@@ -54,9 +54,22 @@ enum {
   DSSD_SESSION_BAD_TOKEN = 1,    /* a draft token outside [0, V)                          */
   DSSD_SESSION_ZERO_RESIDUAL = 2,/* residual mass rounded to 0: token drawn from P_j       */
   DSSD_SESSION_BAD_OFFSETS = 4,  /* draft_offsets not monotone or beyond total_drafts      */
-  DSSD_SESSION_BAD_ROW = 8       /* a softmax sum or maximum that is not finite/positive,
+  DSSD_SESSION_BAD_ROW = 8,      /* a softmax sum or maximum that is not finite/positive,
                                     or an inverse temperature that is not finite/positive  */
+  DSSD_SESSION_SUPPORT_OVERFLOW = 16 /* DSSD_FLAG_SPARSE_SUPPORT was set but the row to draw
+                                    from has more than DSSD_MAX_SUPPORT finite logits        */
 };
+
+/* dssd_batch.flags */
+enum {
+  /* The caller promises that every logits row has at most DSSD_MAX_SUPPORT entries above -inf,
+   * e.g. after top-k filtering upstream (the paper's experiments sample with k = 10; Sec. 4).
+   * verify then also records each row's support while it streams the row, and the two samplers
+   * draw from those few entries instead of passing over the vocabulary again.  Same results as
+   * without the flag up to summation order. */
+  DSSD_FLAG_SPARSE_SUPPORT = 1
+};
+#define DSSD_MAX_SUPPORT 64
 
 /* Input of one verification step for B sessions (Sec. 2.1 "Verification Process";
  * Algorithm 2, inputs of the edge: tokens x_1..x_gamma, values q_j(x_j), and P_1..P_{gamma+1}).
@@ -87,7 +100,7 @@ typedef struct {
                                    accept test at that position, word 1 the residual draw at that
                                    position, word 2 the bonus draw (position gamma_b)              */
   uint32_t session_base;        /* global id of session 0 (keeps results independent of sharding)  */
-  uint32_t reserved;
+  uint32_t flags;               /* DSSD_FLAG_* bits, 0 for none                                    */
   const float *draft_q_tok;     /* [R_Q] or NULL: the scalars q_i(x_i) that DSSD uploads with the
                                    tokens (Sec. 3 "Uplink Transmission"); read only when
                                    draft_probs is NULL                                             */

@@ -12,6 +12,9 @@ LIB_PATH = os.path.join(HERE, "libdssd.so")
 DSSD_F32, DSSD_BF16, DSSD_F16 = 0, 1, 2
 DSSD_OK, DSSD_EINVAL, DSSD_EALIGN, DSSD_ENOMEM, DSSD_EHIP, DSSD_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 SESSION_BAD_TOKEN, SESSION_ZERO_RESIDUAL, SESSION_BAD_OFFSETS, SESSION_BAD_ROW = 1, 2, 4, 8
+SESSION_SUPPORT_OVERFLOW = 16
+FLAG_SPARSE_SUPPORT = 1
+MAX_SUPPORT = 64
 K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
 K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_COUNT = 5, 6, 7, 8, 9
 
@@ -27,7 +30,7 @@ class dssd_batch(C.Structure):
                 ("total_drafts", C.c_int64), ("draft_offsets", C.c_void_p), ("logits", C.c_void_p),
                 ("draft_probs", C.c_void_p), ("draft_tokens", C.c_void_p),
                 ("inv_temperature", C.c_void_p), ("seed", C.c_uint64), ("step", C.c_uint64),
-                ("session_base", C.c_uint32), ("reserved", C.c_uint32), ("draft_q_tok", C.c_void_p)]
+                ("session_base", C.c_uint32), ("flags", C.c_uint32), ("draft_q_tok", C.c_void_p)]
 
 
 class dssd_device_batch(C.Structure):
@@ -197,7 +200,7 @@ def make_device_batch(inputs, p_rows, accepted_len, rejected, out_token, status=
                              status=_dp(status))
 
 
-def make_batch(inputs, seed=0, step=0, session_base=0, q_scalars=None):
+def make_batch(inputs, seed=0, step=0, session_base=0, q_scalars=None, flags=0):
     """dssd_batch from a dict of device tensors as `synth.generate` returns them.  With
     `q_scalars` ([R_Q] fp32) the batch carries those instead of the Q rows (the edge's view)."""
     import torch
@@ -214,7 +217,7 @@ def make_batch(inputs, seed=0, step=0, session_base=0, q_scalars=None):
                       total_drafts=inputs["R_Q"], draft_offsets=_dp(off), logits=_dp(lg),
                       draft_probs=None if q_scalars is not None else _dp(inputs["draft_probs"]),
                       draft_tokens=_dp(inputs["draft_tokens"]),
-                      inv_temperature=_dp(it), seed=seed, step=step, session_base=session_base, reserved=0,
+                      inv_temperature=_dp(it), seed=seed, step=step, session_base=session_base, flags=flags,
                       draft_q_tok=_dp(q_scalars))
 
 

@@ -25,6 +25,9 @@ struct dssd_ctx {
   Job* bonus_job = nullptr;
   int32_t* arrive_resid = nullptr;
   int32_t* arrive_stats = nullptr;
+  int32_t* support_count = nullptr;
+  int32_t* support_idx = nullptr;
+  float* support_z = nullptr;
   uint32_t profile_mask = 0;         // bit k: time kernel k
   bool fused_force = false;          // set by dssd_set_fused_limit with a negative limit: ignore the row-size rule
   int64_t fused_max_blocks = 512;    // dssd_step_fused: largest grid that runs as one launch
@@ -44,7 +47,8 @@ extern "C" size_t dssd_workspace_bytes(int64_t max_rows, int32_t max_V, int32_t 
   const size_t rows = (size_t)max_rows;
   return align256(rows * C * sizeof(float2)) + align256(rows * sizeof(float2)) +
          align256(rows * C * sizeof(float)) + 2 * align256(rows * sizeof(Job)) +
-         align256(2 * rows * sizeof(int32_t));
+         align256(2 * rows * sizeof(int32_t)) + align256(rows * sizeof(int32_t)) +
+         2 * align256(rows * kMaxSupport * sizeof(int32_t));
 }
 
 extern "C" const char* dssd_status_str(dssd_status s) {
@@ -92,7 +96,10 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   c->resid_job = reinterpret_cast<Job*>(p);      p += align256(rows * sizeof(Job));
   c->bonus_job = reinterpret_cast<Job*>(p);      p += align256(rows * sizeof(Job));
   c->arrive_resid = reinterpret_cast<int32_t*>(p);
-  c->arrive_stats = c->arrive_resid + rows;
+  c->arrive_stats = c->arrive_resid + rows;           p += align256(2 * rows * sizeof(int32_t));
+  c->support_count = reinterpret_cast<int32_t*>(p);   p += align256(rows * sizeof(int32_t));
+  c->support_idx = reinterpret_cast<int32_t*>(p);     p += align256(rows * kMaxSupport * sizeof(int32_t));
+  c->support_z = reinterpret_cast<float*>(p);
   // arrival counters start at zero; every kernel that uses them leaves them at zero
   if (hipMemset(c->arrive_resid, 0, 2 * rows * sizeof(int32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
     (void)hipFree(c->workspace);
@@ -121,6 +128,7 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   if (!c || !b || !o) return DSSD_EINVAL;
   if (b->B < 0 || b->V < 1 || b->gamma < 0 || b->total_drafts < 0) return DSSD_EINVAL;
   if (b->logits_dtype != DSSD_F32 && b->logits_dtype != DSSD_BF16) return DSSD_EINVAL;
+  if (b->flags & ~(uint32_t)DSSD_FLAG_SPARSE_SUPPORT) return DSSD_EINVAL;
   if (!b->draft_offsets && b->total_drafts != (int64_t)b->B * b->gamma) return DSSD_EINVAL;
   if (b->B > 0) {
     if (!b->logits) return DSSD_EINVAL;
@@ -148,6 +156,7 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   v->row_stats = o->row_stats; v->p_tok = o->p_tok; v->q_tok = o->q_tok; v->status = o->status;
   v->chunk_stats = c->chunk_stats; v->row_tab = c->row_tab; v->resid_mass = c->resid_mass;
   v->resid_job = c->resid_job; v->bonus_job = c->bonus_job; v->arrive_resid = c->arrive_resid;
+  v->support_count = c->support_count; v->support_idx = c->support_idx; v->support_z = c->support_z;
   return DSSD_OK;
 }
 
@@ -193,10 +202,16 @@ extern "C" dssd_status dssd_verify_batch(dssd_ctx* c, const dssd_batch* b, dssd_
   const int64_t tasks = v.R_L * v.C;
   if ((tasks + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
   const unsigned grid = (unsigned)((tasks + 3) / 4);
+  const bool sparse = (b->flags & DSSD_FLAG_SPARSE_SUPPORT) != 0;
+  if (sparse)   // the rows' support lists start empty (a fill kernel, so the call stays graph-capturable)
+    hipLaunchKernelGGL(zero_i32, dim3((unsigned)((v.R_L + 255) / 256)), dim3(256), 0, s, v.support_count, v.R_L);
   {
     Timed t(c, DSSD_K_ROW_STATS, s);
-    if (bf16) { if (al) DSSD_LAUNCH((row_chunk_stats<true, true>), grid, s, v); else DSSD_LAUNCH((row_chunk_stats<true, false>), grid, s, v); }
-    else      { if (al) DSSD_LAUNCH((row_chunk_stats<false, true>), grid, s, v); else DSSD_LAUNCH((row_chunk_stats<false, false>), grid, s, v); }
+#define DSSD_STATS(BF, AL) do { if (sparse) DSSD_LAUNCH((row_chunk_stats<BF, AL, true>), grid, s, v); \
+                                else DSSD_LAUNCH((row_chunk_stats<BF, AL, false>), grid, s, v); } while (0)
+    if (bf16) { if (al) DSSD_STATS(true, true); else DSSD_STATS(true, false); }
+    else      { if (al) DSSD_STATS(false, true); else DSSD_STATS(false, false); }
+#undef DSSD_STATS
   }
   {
     Timed t(c, DSSD_K_ACCEPT, s);
@@ -214,6 +229,12 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   if (!b->draft_probs) return DSSD_EINVAL;    // the residual needs the full Q rows
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  if (b->flags & DSSD_FLAG_SPARSE_SUPPORT) {   // draw from the recorded support: no pass over V
+    Timed t(c, DSSD_K_RESID_PICK, s);
+    const unsigned g2 = (unsigned)((b->B + 3) / 4);
+    if (bf16) DSSD_LAUNCH((pick_sparse<true, true>), g2, s, v); else DSSD_LAUNCH((pick_sparse<false, true>), g2, s, v);
+    return launch_status();
+  }
   const int32_t groups = (v.C + 3) / 4;
   if ((int64_t)groups * b->B > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
   const unsigned grid = (unsigned)(groups * b->B);
@@ -242,6 +263,12 @@ extern "C" dssd_status dssd_bonus_sample(dssd_ctx* c, const dssd_batch* b, dssd_
   if (st != DSSD_OK || b->B == 0) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  if (b->flags & DSSD_FLAG_SPARSE_SUPPORT) {
+    Timed t(c, DSSD_K_BONUS_PICK, s);
+    const unsigned g2 = (unsigned)((b->B + 3) / 4);
+    if (bf16) DSSD_LAUNCH((pick_sparse<true, false>), g2, s, v); else DSSD_LAUNCH((pick_sparse<false, false>), g2, s, v);
+    return launch_status();
+  }
   {
     Timed t(c, DSSD_K_BONUS_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
@@ -263,7 +290,8 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
   // One launch pays only while the lone workgroup that finishes a session can stream the
   // rejected row (logits + Q) quickly: small grids and rows of a few hundred KiB.
   const int64_t resid_row_bytes = (int64_t)b->V * ((b->logits_dtype == DSSD_BF16 ? 2 : 4) + 4);
-  const bool single = !b->draft_offsets && groups * b->B <= c->fused_max_blocks &&
+  const bool single = !b->draft_offsets && !(b->flags & DSSD_FLAG_SPARSE_SUPPORT) &&
+                      groups * b->B <= c->fused_max_blocks &&
                       (c->fused_force || resid_row_bytes <= (384 << 10));
   if (!single) {
     dssd_status r = dssd_verify_batch(c, b, o, hip_stream);

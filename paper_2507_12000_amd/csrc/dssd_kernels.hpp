@@ -48,6 +48,9 @@ struct BatchView {
   Job* resid_job;                    // [B] rejected sessions: row n
   Job* bonus_job;                    // [B] all-accepted sessions: row gamma_b
   int32_t* arrive_resid;             // [B] chunk masses finished per session; zero between calls
+  int32_t* support_count;            // [R_L] sparse-support mode: finite entries per row
+  int32_t* support_idx;              // [R_L, kMaxSupport]
+  float* support_z;                  // [R_L, kMaxSupport]
 };
 
 __device__ __forceinline__ int64_t session_first_draft(const BatchView& a, int32_t b) {
@@ -72,8 +75,20 @@ template <bool BF16> __device__ __forceinline__ const char* logits_row(const Bat
 // verification process: P(v) = 2^(z_v*c1 - M2)/Z.  This kernel reads every logit exactly once.
 // ---------------------------------------------------------------------------------------
 // (m2_c, s_c) of chunk c of the row at `src`, computed by one wave; every lane gets the result.
-template <bool BF16, bool ALIGNED>
-__device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int32_t V, float c1, int lane) {
+// A row's support: its entries above -inf, at most kMaxSupport of them, in arrival order.
+constexpr int kMaxSupport = 64;
+struct SupportRow {
+  int32_t* count;   // entries seen so far (may exceed kMaxSupport: overflow)
+  int32_t* idx;     // [kMaxSupport] vocabulary indices
+  float* z;         // [kMaxSupport] their logits
+};
+
+// SUPPORT: the wave also appends the chunk's finite entries to the row's support list (rows
+// are expected to be almost entirely -inf, e.g. after top-k filtering, so nearly every chunk
+// skips this at the cost of one wave-uniform branch).
+template <bool BF16, bool ALIGNED, bool SUPPORT = false>
+__device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int32_t V, float c1, int lane,
+                                                 SupportRow sup = SupportRow{}) {
   constexpr int E = Elems<BF16>::per_vec;
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
   float z[kUnroll][E];
@@ -85,7 +100,23 @@ __device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int
   for (int k = 0; k < kUnroll; ++k)
 #pragma unroll
     for (int e = 0; e < E; ++e) mx = fmaxf(mx, z[k][e]);
+  const float lane_mx = mx;
   mx = wave_max(mx);
+  if constexpr (SUPPORT) {
+    if (mx > neg_inf() && lane_mx > neg_inf()) {
+#pragma unroll
+      for (int k = 0; k < kUnroll; ++k)
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          if (z[k][e] > neg_inf()) {
+            const int32_t pos = atomicAdd(sup.count, 1);
+            if (pos < kMaxSupport) {
+              sup.idx[pos] = (int32_t)((v0 + k * kWave) * E + e);
+              sup.z[pos] = z[k][e];
+            }
+          }
+    }
+  }
 
   float m2 = neg_inf(), s = 0.f;
   if (mx > neg_inf()) {
@@ -100,7 +131,7 @@ __device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int
   return make_float2(m2, s);
 }
 
-template <bool BF16, bool ALIGNED>
+template <bool BF16, bool ALIGNED, bool SUPPORT>
 __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
   const int lane = threadIdx.x & 63;
   const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
@@ -109,8 +140,16 @@ __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
   const int32_t c = (int32_t)(task - row * a.C);
   float c1 = kLog2e;
   if (a.inv_temp) c1 *= a.inv_temp[session_of_row(a, row)];
-  const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, row), c, a.V, c1, lane);
+  SupportRow sup{};
+  if constexpr (SUPPORT)
+    sup = SupportRow{a.support_count + row, a.support_idx + row * kMaxSupport, a.support_z + row * kMaxSupport};
+  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, row), c, a.V, c1, lane, sup);
   if (lane == 0) a.chunk_stats[task] = st;
+}
+
+__global__ __launch_bounds__(256) void zero_i32(int32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -510,6 +549,78 @@ __global__ __launch_bounds__(256) void pick_token(const BatchView a) {
   const Job job = RESID ? a.resid_job[b] : a.bonus_job[b];
   if (job.lrow < 0) return;
   pick_for_session<BF16, ALIGNED, RESID>(a, b, job, lane);
+}
+
+// ---------------------------------------------------------------------------------------
+// Sparse-support draw, one wave per session, lane = one entry of the row's support (at most
+// 64 entries above -inf, recorded by row_chunk_stats<..., SUPPORT>).  The same weights and the
+// same inverse-CDF rule in vocabulary order as the dense kernels, on up to 64 entries instead
+// of V: entries are ranked by vocabulary index, moved into rank order with a lane permute, and
+// prefix-summed across the wave.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int32_t draw_from_ranked(float w_ranked, int32_t idx_ranked, float r, int lane) {
+  const float scan = wave_scan(w_ranked, lane);
+  const float total = lane_value(scan, 63);
+  if (!(total > 0.f) || !(total < 3.0e38f)) return -1;
+  const float t = fminf(__fmul_rn(r, total), next_below(total));
+  const uint64_t over = __ballot(scan > t);
+  const int sel = over ? __ffsll((long long)over) - 1 : 63;
+  return __shfl(idx_ranked, sel, kWave);
+}
+
+template <bool BF16, bool RESID>
+__global__ __launch_bounds__(256) void pick_sparse(const BatchView a) {
+  const int lane = threadIdx.x & 63;
+  const int32_t b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (b >= a.B) return;
+  const Job job = RESID ? a.resid_job[b] : a.bonus_job[b];
+  if (job.lrow < 0) return;
+  const int64_t row = job.lrow;
+  const int32_t cnt = a.support_count[row];
+  if (cnt < 1 || cnt > kMaxSupport) {   // the promise of at most 64 finite logits does not hold
+    if (lane == 0) {
+      a.out_token[b] = -1;
+      if (a.status) a.status[b] |= 16;
+    }
+    return;
+  }
+  const int32_t n = (int32_t)(row - b - session_first_draft(a, b));
+  const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
+  const float invZ = 1.f / job.Z;
+  const bool live = lane < cnt;
+  const int32_t idx = live ? a.support_idx[row * kMaxSupport + lane] : 0x7FFFFFFF;
+  const float z = live ? a.support_z[row * kMaxSupport + lane] : neg_inf();
+  const float e = fast_exp2(fmaf(z, c1, -job.M2));                 // 0 for the padding lanes
+  float w = e;
+  if constexpr (RESID) {
+    const float q = live ? a.draft_probs[(row - b) * (int64_t)a.V + idx] : 0.f;
+    w = fmaxf(0.f, fmaf(e, invZ, -q));
+  }
+  // rank = number of entries with a smaller vocabulary index (indices are distinct; padding
+  // lanes carry the largest index and rank after every live entry, among themselves by lane)
+  int32_t rank = 0;
+  for (int32_t m = 0; m < kWave; ++m) {
+    const int32_t im = __shfl(idx, m, kWave);
+    rank += (im < idx || (im == idx && m < lane)) ? 1 : 0;
+  }
+  const int32_t idx_r = __builtin_amdgcn_ds_permute(rank * 4, idx);
+  const float w_r = __builtin_bit_cast(float, __builtin_amdgcn_ds_permute(rank * 4, __builtin_bit_cast(int, w)));
+  const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)n, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi);
+  const float r = u01(rnd.w[RESID ? 1 : 2]);
+  int32_t token = draw_from_ranked(w_r, idx_r, r, lane);
+  bool from_p = false;
+  if (RESID && token < 0) {   // residual mass rounded to zero: draw from P_n instead
+    from_p = true;
+    const float e_r = __builtin_bit_cast(float, __builtin_amdgcn_ds_permute(rank * 4, __builtin_bit_cast(int, e)));
+    token = draw_from_ranked(e_r, idx_r, r, lane);
+  }
+  if (lane == 0) {
+    a.out_token[b] = token;
+    if (a.status) {
+      if (from_p) a.status[b] |= 2;
+      if (token < 0) a.status[b] |= 8;
+    }
+  }
 }
 
 }  // namespace dssd

@@ -336,3 +336,56 @@ def test_non_finite_logits_are_flagged_not_followed(ctx):
     keep = np.array([b not in (2, 5) for b in range(w.B)])
     for k in ("accepted_len", "rejected", "out_token", "status"):
         assert (got[k][keep] == clean[k][keep]).all(), k
+
+
+SPARSE_CASES = [w for w in SMALL if w.top_k] + [
+    synth.Workload("bf16_topk10_big", B=96, V=128256, gamma=8, dtype="bf16", sigmas=(1.0,), top_k=10),
+    synth.Workload("f32_top50", B=20, V=32000, gamma=4, dtype="f32", sigmas=(0.5, 1.5), top_k=50,
+                   temperature_range=(0.6, 1.4)),
+    synth.Workload("bf16_top1_unaligned", B=9, V=4099, gamma=3, dtype="bf16", sigmas=(1.0,), top_k=1),
+]
+
+
+@pytest.mark.parametrize("w", SPARSE_CASES, ids=[w.name for w in SPARSE_CASES])
+def test_sparse_support_mode(ctx, w):
+    """DSSD_FLAG_SPARSE_SUPPORT: the samplers draw from each row's recorded support (at most 64
+    finite logits, as after top-k filtering).  Same answers as the oracle on the same masked
+    rows, and as the library's own dense path."""
+    inputs = synth.generate(w, seed=7, device=DEV)
+    seed, step = 17, 3
+    dense = gpu_step(ctx, inputs, seed, step)
+    batch = D.make_batch(inputs, seed=seed, step=step, flags=D.FLAG_SPARSE_SUPPORT)
+    t, out = D.alloc_out(inputs, DEV)
+    D.dssd_profile_reset(ctx.handle)
+    D.dssd_profile_enable(ctx.handle, True)
+    ctx.step(batch, out)
+    torch.cuda.synchronize()
+    D.dssd_profile_enable(ctx.handle, False)
+    assert D.dssd_profile_read(ctx.handle, D.K_RESID_MASS)[1] == 0        # no pass over V for the redraw
+    got = {k: v.cpu().numpy() for k, v in t.items()}
+    for k in ("accepted_len", "rejected", "p_tok", "q_tok", "row_stats"):
+        assert (got[k] == dense[k]).all(), k
+    h = parity.to_numpy_inputs(inputs)
+    orc = parity.run_oracle(h, seed, step, workers=8)
+    rep = parity.compare(h, got, orc, P_RTOL[w.dtype], seed=seed, step=step)
+    print(f"[parity] sparse {w.name}: {rep}", flush=True)
+    # against the dense path: same tokens except where the draw is a near-tie
+    diff = np.nonzero(got["out_token"] != dense["out_token"])[0]
+    assert all(orc["res"][b]["cdf_margin"] < parity.TIE for b in diff), diff
+    # a second call reuses the (re-zeroed) support lists
+    t2, out2 = D.alloc_out(inputs, DEV)
+    ctx.step(batch, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(t2["out_token"], t["out_token"])
+
+
+def test_sparse_support_overflow_is_reported(ctx):
+    w = synth.Workload("dense_with_flag", B=5, V=3000, gamma=2, dtype="f32", sigmas=(1.0,))
+    inputs = synth.generate(w, seed=1, device=DEV)
+    t, out = D.alloc_out(inputs, DEV)
+    ctx.step(D.make_batch(inputs, seed=1, step=1, flags=D.FLAG_SPARSE_SUPPORT), out)
+    torch.cuda.synchronize()
+    assert (t["out_token"].cpu().numpy() == -1).all()
+    assert (t["status"].cpu().numpy() & D.SESSION_SUPPORT_OVERFLOW).all()
+    bad = D.make_batch(inputs, seed=1, step=1, flags=2)
+    assert D.dssd_verify_batch(ctx.handle, bad, out, 0, check=False) == D.DSSD_EINVAL
