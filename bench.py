@@ -167,6 +167,8 @@ def main():
                          "run the step in sparse-support mode; 0 = the benchmark workload as defined")
     ap.add_argument("--top-k-dense", action="store_true",
                     help="with --top-k: keep the dense samplers (no DSSD_FLAG_SPARSE_SUPPORT)")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="cycle through this many copies of the inputs (defeats cache residency of small batches)")
     ap.add_argument("--split", action="store_true",
                     help="also time the edge/device split path (q scalars up, fp16 P rows down)")
     ap.add_argument("--gpus", type=int, default=1)
@@ -213,8 +215,20 @@ def main():
     ctx = D.Context(dev, max_rows=inputs["R_L"], max_V=w.V)
     batch = D.make_batch(inputs, seed=args.seed, step=0, flags=flags)
     outs, out = D.alloc_out(inputs, dev, debug=False)
+    # --rotate N: N copies of the inputs at different addresses, used in turn, so that a batch
+    # smaller than the chip's 256 MB last-level cache is really read from HBM every step
+    copies = [inputs] + [dict(inputs, logits=inputs["logits"].clone(), draft_probs=inputs["draft_probs"].clone())
+                         for _ in range(max(args.rotate, 1) - 1)]
+    batches = [batch] + [D.make_batch(c, seed=args.seed, step=0, flags=flags) for c in copies[1:]]
 
-    step_fn = ctx.step_fused if args.fused else ctx.step
+    run = ctx.step_fused if args.fused else ctx.step
+
+    def step_fn(_batch, out_):
+        bt = batches[step_fn.count % len(batches)]
+        bt.step = _batch.step
+        step_fn.count += 1
+        run(bt, out_)
+    step_fn.count = 0
     if args.fused_limit is not None:
         D.dssd_set_fused_limit(ctx.handle, args.fused_limit)
     for k in range(args.warmup):
@@ -287,7 +301,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "entry": "dssd_step_fused" if args.fused else
                    "dssd_verify_batch+dssd_residual_sample+dssd_bonus_sample", "B": w.B, "V": w.V, "logits_dtype": w.dtype,
-                   "top_k": args.top_k, "sparse_support": bool(flags & D.FLAG_SPARSE_SUPPORT),
+                   "input_copies_rotated": max(args.rotate, 1), "top_k": args.top_k, "sparse_support": bool(flags & D.FLAG_SPARSE_SUPPORT),
                    "logits_rows": inputs["R_L"], "draft_positions": inputs["R_Q"],
                    "rejected_sessions": int(rejected.sum())},
         "vocab_rows_per_sec": inputs["R_L"] * args.steps / elapsed,
