@@ -57,13 +57,18 @@ _lib = None
 
 
 def load():
-    """Load libdssd.so.  Raises if it has not been built (python -m paper_2507_12000_amd.build)."""
+    """Load libdssd.so, compiling it first if it has never been built.  Raises if neither works."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python paper_2507_12000_amd/build.py` "
-                           "(there is no CPU fallback)")
+        # nothing built yet: compile it now (hipcc); if that is impossible there is nothing to run
+        try:
+            from . import build as _build
+            _build.build()
+        except Exception as e:
+            raise RuntimeError(f"{LIB_PATH} is missing and could not be built ({e}); build it with "
+                               "`python paper_2507_12000_amd/build.py` (there is no CPU fallback)") from e
     L = C.CDLL(LIB_PATH)
     P = C.c_void_p
     L.dssd_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
