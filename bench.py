@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # Valid only for the kernel sources they were taken with: reported as null once those change.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "40e04aad8df49294dd763240753d4d090ee32c201ca8840ccc573fed26bc399b",
-        "bytes_per_launch": int((2426306.6 * 2.0 + 4776.8 * 1.0) * 1024),
+        "sources_sha256": "04dd090dd5a4a1ce41c4699bcd541229aba08bc966e65db50f4cb1d05a72a4ee",
+        "bytes_per_launch": int((2426301.8 * 2.0 + 4776.7 * 1.0) * 1024),
     },
 }
 

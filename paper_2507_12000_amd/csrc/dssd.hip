@@ -12,6 +12,8 @@
 
 using namespace dssd;
 
+static_assert(kMaxSupport == DSSD_MAX_SUPPORT, "header and kernels must agree on the support size");
+
 struct dssd_ctx {
   int device = 0;
   int64_t max_rows = 0;
