@@ -11,7 +11,7 @@ GOLDEN = os.path.join(ROOT, "tests", "golden")
 
 
 def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run on the GPU box only)")
+    config.addinivalue_line("markers", "gpu: needs a real MI355X")
 
 
 @pytest.fixture(scope="session")
