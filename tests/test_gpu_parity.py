@@ -389,3 +389,41 @@ def test_sparse_support_overflow_is_reported(ctx):
     assert (t["status"].cpu().numpy() & D.SESSION_SUPPORT_OVERFLOW).all()
     bad = D.make_batch(inputs, seed=1, step=1, flags=2)
     assert D.dssd_verify_batch(ctx.handle, bad, out, 0, check=False) == D.DSSD_EINVAL
+
+
+def test_gpu_outputs_follow_the_target_law(ctx):
+    """Independent of the oracle: over many steps the token the GPU emits at each position is
+    distributed as the target's P there (chi-square), and the accepted length as prod(beta)."""
+    from scipy import stats
+    V, g, B = 48, 3, 2048
+    gen = torch.Generator(device=DEV); gen.manual_seed(5)
+    z = torch.randn((g + 1, V), generator=gen, device=DEV) * 1.5
+    y = z[:g] + 0.8 * torch.randn((g, V), generator=gen, device=DEV)
+    Q = torch.softmax(y, 1)
+    P = torch.softmax(z.double(), 1).cpu().numpy()
+    Qd = Q.double().cpu().numpy(); Qd /= Qd.sum(1, keepdims=True)
+    beta = np.minimum(P[:g], Qd).sum(1)
+    inputs = dict(logits=z.repeat(B, 1).contiguous(), draft_probs=Q.repeat(B, 1).contiguous(), draft_tokens=None,
+                  draft_offsets=None, inv_temperature=None, B=B, V=V, gamma=g, R_L=B * (g + 1), R_Q=B * g)
+    emitted = np.zeros((g + 1, V), np.int64)
+    n_hist = np.zeros(g + 1, np.int64)
+    for step in range(80):
+        tok = torch.multinomial(Q, B, replacement=True, generator=gen).t().contiguous().to(torch.int32)   # [B, g]
+        inputs["draft_tokens"] = tok.reshape(-1)
+        out = gpu_step(ctx, inputs, 1234, step)
+        n, token, tk = out["accepted_len"], out["out_token"], tok.cpu().numpy()
+        n_hist += np.bincount(n, minlength=g + 1)
+        for i in range(g + 1):
+            reached = n >= i
+            final = np.where(n > i, tk[:, min(i, g - 1)], token)
+            emitted[i] += np.bincount(final[reached], minlength=V)
+    want_n = np.array([np.prod(beta[:k]) * (1 - beta[k]) for k in range(g)] + [np.prod(beta)])
+    assert stats.chisquare(n_hist, want_n * n_hist.sum()).pvalue > 1e-4
+    for i in range(g + 1):
+        exp = P[i] * emitted[i].sum()
+        keep = exp >= 8
+        obs = np.append(emitted[i][keep], emitted[i][~keep].sum())
+        ex = np.append(exp[keep], exp[~keep].sum())
+        if ex[-1] == 0:
+            obs, ex = obs[:-1], ex[:-1]
+        assert stats.chisquare(obs, ex * obs.sum() / ex.sum()).pvalue > 1e-4, i
