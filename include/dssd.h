@@ -153,8 +153,9 @@ dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *
  * bit-identical outputs.  Batches with uniform gamma (draft_offsets == NULL) whose grid is small
  * (at most the limit set by dssd_set_fused_limit workgroups, default 512) and whose rows are
  * short (V * (logit bytes + 4) <= 384 KiB) run as ONE kernel launch, which is what matters when
- * a step is bound by launch latency rather than bandwidth; all others run as the three calls.
- * Needs the full Q rows (draft_probs). */
+ * a step is bound by launch latency rather than bandwidth; small grids with longer rows run as
+ * TWO launches (statistics + accept + bonus, then the redraw of rejected sessions); all others
+ * run as the three calls.  Needs the full Q rows (draft_probs). */
 dssd_status dssd_step_fused(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
 /* Largest grid (workgroups = B * ceil((gamma+1) * chunks_per_row / 4)) that dssd_step_fused runs
  * as a single launch; 0 disables the single-launch path; a negative value sets the limit to its

@@ -292,10 +292,13 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
   // One launch pays only while the lone workgroup that finishes a session can stream the
   // rejected row (logits + Q) quickly: small grids and rows of a few hundred KiB.
   const int64_t resid_row_bytes = (int64_t)b->V * ((b->logits_dtype == DSSD_BF16 ? 2 : 4) + 4);
-  const bool single = !b->draft_offsets && !(b->flags & DSSD_FLAG_SPARSE_SUPPORT) &&
-                      groups * b->B <= c->fused_max_blocks &&
+  const bool fusable = !b->draft_offsets && !(b->flags & DSSD_FLAG_SPARSE_SUPPORT);
+  const bool single = fusable && groups * b->B <= c->fused_max_blocks &&
                       (c->fused_force || resid_row_bytes <= (384 << 10));
-  if (!single) {
+  // Longer rows, still a small grid: statistics + accept + bonus in one launch, the redraw of
+  // rejected sessions in a second one that every workgroup of the chip can share.
+  const bool pair = fusable && !single && groups * b->B <= c->fused_max_blocks;
+  if (!single && !pair) {
     dssd_status r = dssd_verify_batch(c, b, o, hip_stream);
     if (r == DSSD_OK) r = dssd_residual_sample(c, b, o, hip_stream);
     if (r == DSSD_OK) r = dssd_bonus_sample(c, b, o, hip_stream);
@@ -307,8 +310,15 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
     Timed t(c, DSSD_K_FUSED_STEP, s);
     const unsigned grid = (unsigned)(groups * b->B);
     const int32_t g32 = (int32_t)groups;
-    if (bf16) { if (al) DSSD_LAUNCH((fused_small_step<true, true>), grid, s, v, g32, c->arrive_stats); else DSSD_LAUNCH((fused_small_step<true, false>), grid, s, v, g32, c->arrive_stats); }
-    else      { if (al) DSSD_LAUNCH((fused_small_step<false, true>), grid, s, v, g32, c->arrive_stats); else DSSD_LAUNCH((fused_small_step<false, false>), grid, s, v, g32, c->arrive_stats); }
+#define DSSD_FUSED(BF, AL) do { if (single) DSSD_LAUNCH((fused_small_step<BF, AL, true>), grid, s, v, g32, c->arrive_stats); \
+                                else DSSD_LAUNCH((fused_small_step<BF, AL, false>), grid, s, v, g32, c->arrive_stats); } while (0)
+    if (bf16) { if (al) DSSD_FUSED(true, true); else DSSD_FUSED(true, false); }
+    else      { if (al) DSSD_FUSED(false, true); else DSSD_FUSED(false, false); }
+#undef DSSD_FUSED
+  }
+  if (pair && b->total_drafts > 0) {
+    const dssd_status r = launch_status();
+    return r == DSSD_OK ? dssd_residual_sample(c, b, o, hip_stream) : r;
   }
   return launch_status();
 }

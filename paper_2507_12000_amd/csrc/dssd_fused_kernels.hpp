@@ -16,7 +16,9 @@
 
 namespace dssd {
 
-template <bool BF16, bool ALIGNED>
+// TAIL_RESID = false leaves the redraw of rejected sessions to a following resid_mass launch
+// (rows too long for one workgroup to stream alone): two launches instead of four.
+template <bool BF16, bool ALIGNED, bool TAIL_RESID>
 __global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32_t groups, int32_t* arrive_stats) {
   __shared__ int32_t sh_last;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -46,6 +48,7 @@ __global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32
   Job job;
   const int32_t kind = accept_session<BF16>(a, b, &job);
   if (kind == 1) {
+    if constexpr (!TAIL_RESID) return;
     for (int32_t c = wave; c < a.C; c += 4) {
       const float m = resid_chunk_mass<BF16, ALIGNED>(a, b, job, c, lane);
       if (lane == 0) publish(a.resid_mass + (int64_t)b * a.C + c, m);

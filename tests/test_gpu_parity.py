@@ -427,3 +427,24 @@ def test_gpu_outputs_follow_the_target_law(ctx):
         if ex[-1] == 0:
             obs, ex = obs[:-1], ex[:-1]
         assert stats.chisquare(obs, ex * obs.sum() / ex.sum()).pvalue > 1e-4, i
+
+
+def test_fused_step_two_launch_mode(ctx):
+    """A small grid whose rows are too long for one workgroup to stream alone: statistics,
+    accept and bonus run as one launch, the redraw as a second; same outputs as three calls."""
+    w = synth.Workload("pair", B=5, V=128256, gamma=4, dtype="bf16", sigmas=(0.3, 1.5))
+    inputs = synth.generate(w, seed=6, device=DEV)
+    for step in (0, 1):
+        ref = gpu_step(ctx, inputs, 8, step)
+        t, out = D.alloc_out(inputs, DEV)
+        D.dssd_profile_reset(ctx.handle)
+        D.dssd_profile_enable(ctx.handle, True)
+        ctx.step_fused(D.make_batch(inputs, seed=8, step=step), out)
+        torch.cuda.synchronize()
+        D.dssd_profile_enable(ctx.handle, False)
+        launches = {D.kernel_name(k): D.dssd_profile_read(ctx.handle, k)[1] for k in range(D.K_COUNT)}
+        assert launches["fused_small_step"] == 1 and launches["resid_mass"] == 1
+        assert launches["row_chunk_stats"] == 0 and launches["accept_scan"] == 0 and launches["bonus_pick"] == 0
+        for k in ref:
+            assert (ref[k] == t[k].cpu().numpy()).all(), (k, step)
+    assert 0 < ref["rejected"].sum() < w.B
