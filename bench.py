@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # Valid only for the kernel sources they were taken with: reported as null once those change.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "86f7831ca5011ad3882eb4fc281c34ef6b6d247e2aa76b200694fc8d31787668",
+        "sources_sha256": "c9714a9717d83ba2c2a7c707341b9790ee99a1c6842dfe5db5a48aa4dd67ed5b",
         "bytes_per_launch": int((2426301.8 * 2.0 + 4776.7 * 1.0) * 1024),
     },
 }
@@ -313,6 +313,23 @@ def main():
                      "traffic": traffic, "algorithmic_bytes_per_launch": dom_bytes,
                      "avg_launch_us": k1_us},
     }
+    # read ceiling of this chip for the statistics kernel's access pattern, over the same buffer
+    lg = inputs["logits"]
+    nbytes = lg.numel() * lg.element_size()
+    if nbytes >= (256 << 20):
+        for _ in range(3):
+            D.dssd_probe_read(ctx.handle, lg.data_ptr(), nbytes, ctx.stream())
+        torch.cuda.synchronize()
+        D.dssd_profile_reset(ctx.handle)
+        D.dssd_profile_enable(ctx.handle, 1 << D.K_READ_PROBE)
+        for _ in range(20):
+            D.dssd_probe_read(ctx.handle, lg.data_ptr(), nbytes, ctx.stream())
+        torch.cuda.synchronize()
+        D.dssd_profile_enable(ctx.handle, False)
+        ms, n = D.dssd_profile_read(ctx.handle, D.K_READ_PROBE)
+        ceiling = (nbytes // 8192) * 8192 / (ms / n * 1e-3) / 1e9
+        result["roofline"]["measured_read_ceiling_GBps"] = ceiling
+        result["roofline"]["frac_of_measured_read_ceiling"] = achieved / ceiling
     if args.split:
         result["split_path"] = time_split_path(ctx, D, torch, inputs, outs, args)
     if not args.no_cpu_baseline:

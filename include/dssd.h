@@ -202,16 +202,21 @@ const char *dssd_status_str(dssd_status s);
  * microseconds of queue time, so time only the kernels a measurement needs.  Kernel ids: 0 row softmax statistics,
  * 1 accept / first-reject, 2 residual chunk masses (for small batches also the pick, in one
  * launch), 3 residual pick, 4 bonus pick, 5 export of P rows, 6 and 7 chunk masses and pick of
- * the device-side redraw, 8 the single-launch step of dssd_step_fused. */
+ * the device-side redraw, 8 the single-launch step of dssd_step_fused, 9 the read probe. */
 enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
        DSSD_K_BONUS_PICK = 4, DSSD_K_EXPORT_P = 5, DSSD_K_DEVICE_MASS = 6, DSSD_K_DEVICE_PICK = 7,
-       DSSD_K_FUSED_STEP = 8, DSSD_K_COUNT = 9 };
+       DSSD_K_FUSED_STEP = 8, DSSD_K_READ_PROBE = 9, DSSD_K_COUNT = 10 };
 dssd_status dssd_profile_enable(dssd_ctx *ctx, uint32_t kernel_mask);
 /* Synchronises the recorded events, returns the summed duration (ms) and number of launches
  * of one kernel since the last reset. */
 dssd_status dssd_profile_read(dssd_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
 dssd_status dssd_profile_reset(dssd_ctx *ctx);
 const char *dssd_kernel_name(int kernel_id);
+
+/* Measurement aid: read `bytes` (rounded down to 8 KiB) of device memory at `buf` (16-byte
+ * aligned) with the access pattern of the row-statistics kernel and no arithmetic.  Its rate is
+ * the read ceiling that kernel can be held against on the chip at hand. */
+dssd_status dssd_probe_read(dssd_ctx *ctx, const void *buf, size_t bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -16,13 +16,13 @@ SESSION_SUPPORT_OVERFLOW = 16
 FLAG_SPARSE_SUPPORT = 1
 MAX_SUPPORT = 64
 K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
-K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_COUNT = 5, 6, 7, 8, 9
+K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_COUNT = 5, 6, 7, 8, 9, 10
 
 # every symbol include/dssd.h declares
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
            "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_status_str", "dssd_profile_enable",
-           "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name")
+           "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name", "dssd_probe_read")
 
 
 class dssd_batch(C.Structure):
@@ -87,6 +87,8 @@ def load():
     L.dssd_export_p_rows.restype = C.c_int
     L.dssd_residual_sample_from_p.argtypes = [P, C.POINTER(dssd_device_batch), P]
     L.dssd_residual_sample_from_p.restype = C.c_int
+    L.dssd_probe_read.argtypes = [P, P, C.c_size_t, P]
+    L.dssd_probe_read.restype = C.c_int
     L.dssd_status_str.argtypes = [C.c_int]
     L.dssd_status_str.restype = C.c_char_p
     L.dssd_kernel_name.argtypes = [C.c_int]
@@ -164,6 +166,13 @@ def dssd_residual_sample_from_p(ctx, device_batch, stream=0, check=True):
     rc = load().dssd_residual_sample_from_p(ctx, C.byref(device_batch), C.c_void_p(stream or 0))
     if check and rc != DSSD_OK:
         raise DssdError(rc, "dssd_residual_sample_from_p")
+    return rc
+
+
+def dssd_probe_read(ctx, ptr, nbytes, stream=0):
+    rc = load().dssd_probe_read(ctx, C.c_void_p(ptr), int(nbytes), C.c_void_p(stream or 0))
+    if rc != DSSD_OK:
+        raise DssdError(rc, "dssd_probe_read")
     return rc
 
 

@@ -68,7 +68,7 @@ extern "C" const char* dssd_status_str(dssd_status s) {
 extern "C" const char* dssd_kernel_name(int k) {
   static const char* names[DSSD_K_COUNT] = {"row_chunk_stats", "accept_scan", "resid_mass", "resid_pick",
                                             "bonus_pick", "export_p_rows", "device_resid_mass",
-                                            "device_resid_pick", "fused_small_step"};
+                                            "device_resid_pick", "fused_small_step", "read_probe"};
   return (k >= 0 && k < DSSD_K_COUNT) ? names[k] : "?";
 }
 
@@ -394,6 +394,21 @@ extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_devic
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     if (f16) { if (al) DSSD_LAUNCH((device_pick<true, true>), g2, s, d); else DSSD_LAUNCH((device_pick<true, false>), g2, s, d); }
     else     { if (al) DSSD_LAUNCH((device_pick<false, true>), g2, s, d); else DSSD_LAUNCH((device_pick<false, false>), g2, s, d); }
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_probe_read(dssd_ctx* c, const void* buf, size_t bytes, void* hip_stream) {
+  if (!c || !buf) return DSSD_EINVAL;
+  if (reinterpret_cast<uintptr_t>(buf) & 15) return DSSD_EALIGN;
+  const int64_t chunks = (int64_t)(bytes / (kChunkVecs * 16));
+  if (chunks == 0) return DSSD_OK;
+  if ((chunks + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  {
+    Timed t(c, DSSD_K_READ_PROBE, s);
+    hipLaunchKernelGGL(read_probe, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, s,
+                       static_cast<const u32x4*>(buf), chunks, reinterpret_cast<uint32_t*>(c->resid_mass));
   }
   return launch_status();
 }

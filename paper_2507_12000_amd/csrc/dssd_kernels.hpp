@@ -152,6 +152,23 @@ __global__ __launch_bounds__(256) void zero_i32(int32_t* p, int64_t n) {
   if (i < n) p[i] = 0;
 }
 
+// Measurement aid: the access pattern of row_chunk_stats (one wave per 8 KiB, eight non-temporal
+// 128-bit loads per lane, XCD-contiguous block order) with no arithmetic but an OR.  What this
+// reaches is the read bandwidth the statistics kernel can be held against on a given chip.
+__global__ __launch_bounds__(256) void read_probe(const u32x4* src, int64_t chunks, uint32_t* sink) {
+  const int lane = threadIdx.x & 63;
+  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
+  if (task >= chunks) return;
+  const u32x4* p = src + task * kChunkVecs + lane;
+  uint32_t acc = 0;
+  u32x4 v[kUnroll];
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) v[k] = __builtin_nontemporal_load(p + k * kWave);
+#pragma unroll
+  for (int k = 0; k < kUnroll; ++k) acc |= v[k][0] | v[k][1] | v[k][2] | v[k][3];
+  if (acc == 0x5EEDF00Du) sink[0] = acc;   // keeps the loads alive; practically never taken
+}
+
 // ---------------------------------------------------------------------------------------
 // Accept / reject and first-reject scan, one workgroup per session.
 // Algorithm 2, "Verification Process" loop: accept x_i iff r_i < min(1, p_i(x_i)/q_i(x_i)),
