@@ -448,3 +448,25 @@ def test_fused_step_two_launch_mode(ctx):
         for k in ref:
             assert (ref[k] == t[k].cpu().numpy()).all(), (k, step)
     assert 0 < ref["rejected"].sum() < w.B
+
+
+def test_inconsistent_offsets_are_reported_per_session(ctx):
+    """A draft_offsets table that is not monotone or runs past total_drafts: the sessions it
+    breaks are flagged (BAD_OFFSETS) and skipped; no access leaves the buffers."""
+    w = synth.Workload("offsets", B=4, V=3000, gamma=0, dtype="f32", gamma_range=(3, 3), sigmas=(1.0,))
+    inputs = synth.generate(w, seed=2, device=DEV)
+    good = gpu_step(ctx, inputs, 6, 0)
+    assert (good["status"] == 0).all()
+    broken = dict(inputs)
+    off = inputs["draft_offsets"].clone()          # [0, 3, 6, 9, 12]
+    off[2] = 2                                     # session 1 = [3, 2): negative length; session 2 = [2, 9)
+    off[4] = 13                                    # session 3 runs past total_drafts = 12
+    broken["draft_offsets"] = off
+    got = gpu_step(ctx, broken, 6, 0)
+    assert got["status"][1] == D.SESSION_BAD_OFFSETS and got["status"][3] == D.SESSION_BAD_OFFSETS
+    for b in (1, 3):
+        assert (got["accepted_len"][b], got["rejected"][b], got["out_token"][b]) == (0, 1, -1)
+    assert got["status"][0] == 0 and got["status"][2] == 0
+    for k in ("accepted_len", "rejected", "out_token"):
+        assert got[k][0] == good[k][0]             # session 0 is untouched by its neighbours' trouble
+    assert 0 <= got["out_token"][2] < w.V
