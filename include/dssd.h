@@ -155,12 +155,16 @@ dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *
  * short (V * (logit bytes + 4) <= 384 KiB) run as ONE kernel launch, which is what matters when
  * a step is bound by launch latency rather than bandwidth; small grids with longer rows run as
  * TWO launches (statistics + accept + bonus, then the redraw of rejected sessions); all others
- * run as the three calls.  Needs the full Q rows (draft_probs). */
+ * run the kernels of the three calls, with the bonus draw folded into the accept launch when
+ * the rows are dense (one launch fewer).  Needs the full Q rows (draft_probs). */
 dssd_status dssd_step_fused(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
 /* Largest grid (workgroups = B * ceil((gamma+1) * chunks_per_row / 4)) that dssd_step_fused runs
  * as a single launch; 0 disables the single-launch path; a negative value sets the limit to its
  * magnitude and lifts the row-length rule (for tests and measurements). */
 dssd_status dssd_set_fused_limit(dssd_ctx *ctx, int64_t max_blocks);
+/* Largest grid that dssd_step_fused runs as two launches when the single-launch rule does not
+ * apply; 0 disables the two-launch path.  Negative values are DSSD_EINVAL. */
+dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
 
 /* Edge side, Algorithm 2 "Downlink Transmission": after dssd_verify_batch, for every session
  * with rejected = 1 write the distribution at the rejected position, P_n(v) for v in [0, V), into

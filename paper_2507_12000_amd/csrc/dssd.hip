@@ -33,6 +33,7 @@ struct dssd_ctx {
   uint32_t profile_mask = 0;         // bit k: time kernel k
   bool fused_force = false;          // set by dssd_set_fused_limit with a negative limit: ignore the row-size rule
   int64_t fused_max_blocks = 512;    // dssd_step_fused: largest grid that runs as one launch
+  int64_t pair_max_blocks = 512;     // dssd_step_fused: largest grid that runs as two launches
   std::vector<hipEvent_t> ev_begin[DSSD_K_COUNT], ev_end[DSSD_K_COUNT];
   size_t ev_used[DSSD_K_COUNT] = {};
 };
@@ -195,11 +196,10 @@ struct Timed {
 
 static dssd_status launch_status() { return hipGetLastError() == hipSuccess ? DSSD_OK : DSSD_EHIP; }
 
-extern "C" dssd_status dssd_verify_batch(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
-  BatchView v;
-  const dssd_status st = check_and_view(c, b, o, &v);
-  if (st != DSSD_OK || b->B == 0) return st;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+// Row statistics, then accept / first-reject per session.  tail_bonus: the accept kernel also
+// draws the bonus token of all-accepted sessions (dense rows only).
+static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const BatchView& v, hipStream_t s,
+                                   bool tail_bonus) {
   const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
   const int64_t tasks = v.R_L * v.C;
   if ((tasks + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
@@ -218,9 +218,21 @@ extern "C" dssd_status dssd_verify_batch(dssd_ctx* c, const dssd_batch* b, dssd_
   {
     Timed t(c, DSSD_K_ACCEPT, s);
     const unsigned g2 = (unsigned)b->B;   // one workgroup per session
-    if (bf16) DSSD_LAUNCH((accept_scan<true>), g2, s, v); else DSSD_LAUNCH((accept_scan<false>), g2, s, v);
+    if (tail_bonus && !sparse) {
+      if (bf16) { if (al) DSSD_LAUNCH((accept_scan_bonus<true, true>), g2, s, v); else DSSD_LAUNCH((accept_scan_bonus<true, false>), g2, s, v); }
+      else      { if (al) DSSD_LAUNCH((accept_scan_bonus<false, true>), g2, s, v); else DSSD_LAUNCH((accept_scan_bonus<false, false>), g2, s, v); }
+    } else {
+      if (bf16) DSSD_LAUNCH((accept_scan<true>), g2, s, v); else DSSD_LAUNCH((accept_scan<false>), g2, s, v);
+    }
   }
   return launch_status();
+}
+
+extern "C" dssd_status dssd_verify_batch(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
+  BatchView v;
+  const dssd_status st = check_and_view(c, b, o, &v);
+  if (st != DSSD_OK || b->B == 0) return st;
+  return verify_launches(c, b, v, static_cast<hipStream_t>(hip_stream), false);
 }
 
 extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
@@ -297,11 +309,14 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
                       (c->fused_force || resid_row_bytes <= (384 << 10));
   // Longer rows, still a small grid: statistics + accept + bonus in one launch, the redraw of
   // rejected sessions in a second one that every workgroup of the chip can share.
-  const bool pair = fusable && !single && groups * b->B <= c->fused_max_blocks;
+  const bool pair = fusable && !single && groups * b->B <= c->pair_max_blocks;
   if (!single && !pair) {
-    dssd_status r = dssd_verify_batch(c, b, o, hip_stream);
+    // The streaming kernels, with the bonus draw folded into the accept launch where the rows
+    // are dense: one launch fewer than the three calls, the same device functions.
+    const bool sparse = (b->flags & DSSD_FLAG_SPARSE_SUPPORT) != 0;
+    dssd_status r = verify_launches(c, b, v, static_cast<hipStream_t>(hip_stream), true);
     if (r == DSSD_OK) r = dssd_residual_sample(c, b, o, hip_stream);
-    if (r == DSSD_OK) r = dssd_bonus_sample(c, b, o, hip_stream);
+    if (r == DSSD_OK && sparse) r = dssd_bonus_sample(c, b, o, hip_stream);
     return r;
   }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -327,6 +342,12 @@ extern "C" dssd_status dssd_set_fused_limit(dssd_ctx* c, int64_t max_blocks) {
   if (!c) return DSSD_EINVAL;
   c->fused_force = max_blocks < 0;
   c->fused_max_blocks = max_blocks < 0 ? -max_blocks : max_blocks;
+  return DSSD_OK;
+}
+
+extern "C" dssd_status dssd_set_fused_pair_limit(dssd_ctx* c, int64_t max_blocks) {
+  if (!c || max_blocks < 0) return DSSD_EINVAL;
+  c->pair_max_blocks = max_blocks;
   return DSSD_OK;
 }
 

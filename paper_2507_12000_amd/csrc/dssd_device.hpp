@@ -148,9 +148,11 @@ __device__ __forceinline__ void load_probs(const float* row, int64_t e0, int32_t
 
 // ------------------------------------------------------------------ cross-workgroup hand-over
 // A value written by one workgroup and read by another inside the same launch.  publish()
-// writes it through to the device-coherent level, arrive() waits for this wave's published
-// stores to complete and then bumps a counter, observe() reads at the device-coherent level.
-// No cache-wide write-back or invalidate is involved, so streaming waves are not disturbed.
+// writes it through to the device-coherent level, stores_done() holds the wave until every
+// store it has issued is acknowledged there, arrive() does that and then bumps a counter,
+// observe() reads at the device-coherent level.  A reader that saw the counter complete
+// therefore finds every value published before the matching arrive().  No cache-wide
+// write-back or invalidate is involved, so streaming waves are not disturbed.
 __device__ __forceinline__ void publish(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -166,8 +168,16 @@ __device__ __forceinline__ float2 observe2(const float2* p) {
       __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return make_float2(as_float((uint32_t)bits), as_float((uint32_t)(bits >> 32)));
 }
+// A workgroup-scope release fence orders the compiler but emits no wait on this target (the
+// waves of a workgroup share one vector cache), and the counter usually lives in another
+// memory channel than the published values: without the explicit wait the increment could be
+// performed before a published store has landed.
+__device__ __forceinline__ void stores_done() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
 __device__ __forceinline__ int32_t arrive(int32_t* counter) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's stores have completed
+  stores_done();
   return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32
     const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, lrow0 + i), c, a.V, c1, lane);
     if (lane == 0) {
       publish2(a.chunk_stats + (lrow0 + i) * a.C + c, st);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the store has completed
+      stores_done();   // acknowledged before the barrier that precedes the arrival
     }
   }
   __syncthreads();
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32
       const float m = resid_chunk_mass<BF16, ALIGNED>(a, b, job, c, lane);
       if (lane == 0) publish(a.resid_mass + (int64_t)b * a.C + c, m);
     }
-    if (lane == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) stores_done();
     __syncthreads();
     if (wave == 0) pick_for_session<BF16, ALIGNED, true>(a, b, job, lane);
   } else if (kind == 2) {

@@ -568,6 +568,16 @@ __global__ __launch_bounds__(256) void pick_token(const BatchView a) {
   pick_for_session<BF16, ALIGNED, RESID>(a, b, job, lane);
 }
 
+// accept_scan that also draws the bonus token of an all-accepted session (Algorithm 1 runs the
+// two back to back at the edge): the session's workgroup already holds the last row's merged
+// statistics, so the draw costs one chunk re-read and saves a launch.
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(256) void accept_scan_bonus(const BatchView a) {
+  Job job;
+  const int32_t kind = accept_session<BF16>(a, blockIdx.x, &job);
+  if (kind == 2 && threadIdx.x < kWave) pick_for_session<BF16, ALIGNED, false>(a, blockIdx.x, job, threadIdx.x);
+}
+
 // ---------------------------------------------------------------------------------------
 // Sparse-support draw, one wave per session, lane = one entry of the row's support (at most
 // 64 entries above -inf, recorded by row_chunk_stats<..., SUPPORT>).  The same weights and the

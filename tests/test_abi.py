@@ -60,6 +60,7 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert D.load().dssd_verify_batch(None, None, None, None) == D.DSSD_EINVAL
     assert D.load().dssd_profile_enable(None, 1) == D.DSSD_EINVAL
     assert D.load().dssd_set_fused_limit(None, 1) == D.DSSD_EINVAL
+    assert D.load().dssd_set_fused_pair_limit(None, 1) == D.DSSD_EINVAL
     assert D.status_str(D.DSSD_EALIGN) == "misaligned pointer"
     assert D.kernel_name(D.K_ROW_STATS) == "row_chunk_stats"
     assert D.dssd_workspace_bytes(0, 10) == 0 and D.dssd_workspace_bytes(100, 32000) > 100 * 16 * 8

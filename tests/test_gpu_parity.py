@@ -231,20 +231,35 @@ def test_fused_step_equals_three_calls(ctx, w):
         D.dssd_set_fused_limit(ctx.handle, 512)
 
 
-def test_fused_step_falls_back_for_ragged_and_large(ctx):
-    w = synth.Workload("fused_ragged", B=21, V=7000, gamma=0, dtype="bf16", gamma_range=(1, 5))
+FALLBACK_CASES = [
+    synth.Workload("fused_ragged", B=21, V=7000, gamma=0, dtype="bf16", gamma_range=(1, 5),
+                   frac_q_equals_p=0.3),
+    synth.Workload("fused_large_f32", B=300, V=9000, gamma=3, dtype="f32", sigmas=(0.1, 0.5),
+                   frac_q_equals_p=0.2),
+    synth.Workload("fused_odd_V_bf16", B=130, V=33333, gamma=4, dtype="bf16", sigmas=(0.2,),
+                   temperature_range=(0.7, 1.3)),
+]
+
+
+@pytest.mark.parametrize("w", FALLBACK_CASES, ids=[w.name for w in FALLBACK_CASES])
+def test_fused_step_streams_ragged_and_large_batches(ctx, w):
+    """Batches the single launch does not take run the streaming kernels with the bonus draw
+    folded into the accept launch: same outputs as the three calls, one launch fewer."""
     inputs = synth.generate(w, seed=3, device=DEV)
-    ref = gpu_step(ctx, inputs, 4, 0)
-    t, out = D.alloc_out(inputs, DEV)
-    D.dssd_profile_reset(ctx.handle)
-    D.dssd_profile_enable(ctx.handle, True)
-    ctx.step_fused(D.make_batch(inputs, seed=4, step=0), out)
-    torch.cuda.synchronize()
-    D.dssd_profile_enable(ctx.handle, False)
-    assert D.dssd_profile_read(ctx.handle, D.K_FUSED_STEP)[1] == 0
-    assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)[1] == 1
-    for k in ref:
-        assert (ref[k] == t[k].cpu().numpy()).all(), k
+    for step in (0, 1):
+        ref = gpu_step(ctx, inputs, 4, step)
+        assert (ref["rejected"] == 0).any() and (ref["rejected"] == 1).any()
+        t, out = D.alloc_out(inputs, DEV)
+        D.dssd_profile_reset(ctx.handle)
+        D.dssd_profile_enable(ctx.handle, True)
+        ctx.step_fused(D.make_batch(inputs, seed=4, step=step), out)
+        torch.cuda.synchronize()
+        D.dssd_profile_enable(ctx.handle, False)
+        assert D.dssd_profile_read(ctx.handle, D.K_FUSED_STEP)[1] == 0
+        assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)[1] == 1
+        assert D.dssd_profile_read(ctx.handle, D.K_BONUS_PICK)[1] == 0
+        for k in ref:
+            assert (ref[k] == t[k].cpu().numpy()).all(), (k, step)
 
 
 EXTREME = [
