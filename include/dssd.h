@@ -222,6 +222,15 @@ const char *dssd_kernel_name(int kernel_id);
  * the read ceiling that kernel can be held against on the chip at hand. */
 dssd_status dssd_probe_read(dssd_ctx *ctx, const void *buf, size_t bytes, void *hip_stream);
 
+/* Checking aid: the Philox4x32-10 blocks the step draws from, for the rectangle of sessions
+ * [session_first, +n_sessions) x positions [position_first, +n_positions) (32-bit wrap-around),
+ * counter = (session_base + b, position, step low, step high), key = (seed low, seed high).
+ * words (device, 4-byte aligned) receives n_sessions * n_positions * 4 uint32: word 0 feeds the
+ * accept test r_j of Algorithm 2, word 1 the redraw, word 2 the bonus draw, word 3 is unused. */
+dssd_status dssd_random_words(dssd_ctx *ctx, uint64_t seed, uint64_t step, uint32_t session_first,
+                              uint32_t position_first, int32_t n_sessions, int32_t n_positions,
+                              uint32_t *words, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_COUNT = 
 # every symbol include/dssd.h declares
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
-           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_status_str", "dssd_profile_enable",
+           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_random_words", "dssd_status_str", "dssd_profile_enable",
            "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name", "dssd_probe_read")
 
 
@@ -79,6 +79,8 @@ def load():
     L.dssd_destroy.restype = None
     L.dssd_set_fused_limit.argtypes = [P, C.c_int64]
     L.dssd_set_fused_limit.restype = C.c_int
+    L.dssd_random_words.argtypes = [P, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32, P, P]
+    L.dssd_random_words.restype = C.c_int
     L.dssd_set_fused_pair_limit.argtypes = [P, C.c_int64]
     L.dssd_set_fused_pair_limit.restype = C.c_int
     for name in ("dssd_verify_batch", "dssd_residual_sample", "dssd_bonus_sample", "dssd_step_fused"):
@@ -155,6 +157,11 @@ def dssd_step_fused(ctx, batch, out, stream=0, check=True):
 
 def dssd_set_fused_limit(ctx, max_blocks):
     return load().dssd_set_fused_limit(ctx, int(max_blocks))
+
+
+def dssd_random_words(ctx, seed, step, session_first, position_first, n_sessions, n_positions, words_ptr, stream):
+    return load().dssd_random_words(ctx, seed, step, session_first, position_first, n_sessions, n_positions,
+                                    words_ptr, stream)
 
 
 def dssd_set_fused_pair_limit(ctx, max_blocks):

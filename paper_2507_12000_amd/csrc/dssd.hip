@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "dssd_fused_kernels.hpp"
+#include "dssd_util_kernels.hpp"
 #include "dssd_split_kernels.hpp"
 
 using namespace dssd;
@@ -431,6 +432,22 @@ extern "C" dssd_status dssd_probe_read(dssd_ctx* c, const void* buf, size_t byte
     hipLaunchKernelGGL(read_probe, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, s,
                        static_cast<const u32x4*>(buf), chunks, reinterpret_cast<uint32_t*>(c->resid_mass));
   }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_random_words(dssd_ctx* c, uint64_t seed, uint64_t step, uint32_t session_first,
+                                         uint32_t position_first, int32_t n_sessions, int32_t n_positions,
+                                         uint32_t* words, void* hip_stream) {
+  if (!c || n_sessions < 0 || n_positions < 0) return DSSD_EINVAL;
+  const int64_t n = (int64_t)n_sessions * n_positions;
+  if (n == 0) return DSSD_OK;
+  if (!words) return DSSD_EINVAL;
+  if (reinterpret_cast<uintptr_t>(words) & 3) return DSSD_EALIGN;
+  if ((n + 255) / 256 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+  hipLaunchKernelGGL(random_words, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), session_first, position_first, n_sessions,
+                     n_positions, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t)seed, (uint32_t)(seed >> 32),
+                     words);
   return launch_status();
 }
 

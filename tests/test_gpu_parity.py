@@ -485,3 +485,40 @@ def test_inconsistent_offsets_are_reported_per_session(ctx):
     for k in ("accepted_len", "rejected", "out_token"):
         assert got[k][0] == good[k][0]             # session 0 is untouched by its neighbours' trouble
     assert 0 <= got["out_token"][2] < w.V
+
+
+def _gpu_words(ctx, seed, step, s0, p0, ns, npos):
+    words = torch.zeros(ns * npos * 4, dtype=torch.int32, device=DEV)
+    st = D.dssd_random_words(ctx.handle, seed, step, s0, p0, ns, npos, words.data_ptr(), ctx.stream())
+    assert st == D.DSSD_OK
+    torch.cuda.synchronize()
+    return words.cpu().numpy().view(np.uint32).reshape(ns, npos, 4)
+
+
+def test_random_blocks_match_the_published_vectors_and_the_oracle(ctx):
+    """The generator inside the kernels, word for word: the published known-answer vectors of
+    Philox4x32-10 (tests/golden) and the oracle's block on a rectangle of (session, position)
+    with 64-bit seed and step, including the 32-bit wrap of the session index."""
+    import os
+    kat = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    n = 0
+    for line in open(kat):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = [int(x, 16) for x in line.split()]
+        ctr, key, want = f[0:4], f[4:6], f[6:10]
+        got = _gpu_words(ctx, key[0] | (key[1] << 32), ctr[2] | (ctr[3] << 32), ctr[0], ctr[1], 1, 1)
+        assert [int(x) for x in got[0, 0]] == want, line
+        n += 1
+    assert n == 3
+    from oracle import oracle as O
+    seed, step = 0xFEDCBA9876543210, 0x1234567890ABCDEF
+    s0, p0, ns, npos = 0xFFFFFFF0, 0, 40, 70          # sessions wrap past 2^32
+    got = _gpu_words(ctx, seed, step, s0, p0, ns, npos)
+    for s in range(ns):
+        for p in range(0, npos, 7):
+            want = O.random_block(seed, step, (s0 + s) & 0xFFFFFFFF, p0 + p)
+            assert (got[s, p] == want).all(), (s, p)
+    assert D.dssd_random_words(ctx.handle, 0, 0, 0, 0, -1, 1, 0, ctx.stream()) == D.DSSD_EINVAL
+    assert D.dssd_random_words(ctx.handle, 0, 0, 0, 0, 1, 1, 0, ctx.stream()) == D.DSSD_EINVAL
+    assert D.dssd_random_words(ctx.handle, 0, 0, 0, 0, 0, 5, 0, ctx.stream()) == D.DSSD_OK
