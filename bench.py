@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # Valid only for the kernel sources they were taken with: reported as null once those change.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "ffbd1509606f1fad001ada00d04727d51c3593acd831d61b6cb8d39d203c96e9",
-        "bytes_per_launch": int((2426304.0 * 2.0 + 4776.8 * 1.0) * 1024),
+        "sources_sha256": "8efa39390b174b5cdfc11862a5ffafc20d18ba55c6a5dc17e15fe9434683d350",
+        "bytes_per_launch": int((2426309.2 * 2.0 + 4776.7 * 1.0) * 1024),
     },
 }
 

@@ -104,6 +104,12 @@ typedef struct {
   const float *draft_q_tok;     /* [R_Q] or NULL: the scalars q_i(x_i) that DSSD uploads with the
                                    tokens (Sec. 3 "Uplink Transmission"); read only when
                                    draft_probs is NULL                                             */
+  const uint64_t *step_counter; /* device, 8-byte aligned, or NULL: a counter read by the kernels
+                                   when they run and ADDED to `step` (64-bit wrap).  For callers
+                                   that record the calls into a HIP graph: `step` is frozen into
+                                   the graph, this is not, so bumping it between replays gives
+                                   every replay fresh random numbers.  It must not change while
+                                   the calls of one step are in flight                             */
 } dssd_batch;
 
 /* Output of one step: the paper's (x_j, j) record per session plus what the samplers and the
@@ -190,6 +196,7 @@ typedef struct {
   uint32_t session_base, reserved;
   int32_t *out_token;           /* [B] written for rejected sessions only                           */
   int32_t *status;              /* [B] or NULL: DSSD_SESSION_* bits (written for rejected sessions) */
+  const uint64_t *step_counter; /* device or NULL: as in dssd_batch                                 */
 } dssd_device_batch;
 
 /* Device side, Algorithm 2 "Resample" from what crossed the link: for every rejected session,

@@ -30,7 +30,8 @@ class dssd_batch(C.Structure):
                 ("total_drafts", C.c_int64), ("draft_offsets", C.c_void_p), ("logits", C.c_void_p),
                 ("draft_probs", C.c_void_p), ("draft_tokens", C.c_void_p),
                 ("inv_temperature", C.c_void_p), ("seed", C.c_uint64), ("step", C.c_uint64),
-                ("session_base", C.c_uint32), ("flags", C.c_uint32), ("draft_q_tok", C.c_void_p)]
+                ("session_base", C.c_uint32), ("flags", C.c_uint32), ("draft_q_tok", C.c_void_p),
+                ("step_counter", C.c_void_p)]
 
 
 class dssd_device_batch(C.Structure):
@@ -38,7 +39,8 @@ class dssd_device_batch(C.Structure):
                 ("total_drafts", C.c_int64), ("draft_offsets", C.c_void_p), ("draft_probs", C.c_void_p),
                 ("p_rows", C.c_void_p), ("accepted_len", C.c_void_p), ("rejected", C.c_void_p),
                 ("seed", C.c_uint64), ("step", C.c_uint64), ("session_base", C.c_uint32),
-                ("reserved", C.c_uint32), ("out_token", C.c_void_p), ("status", C.c_void_p)]
+                ("reserved", C.c_uint32), ("out_token", C.c_void_p), ("status", C.c_void_p),
+                ("step_counter", C.c_void_p)]
 
 
 class dssd_out(C.Structure):
@@ -213,7 +215,7 @@ def _dp(t):
 
 
 def make_device_batch(inputs, p_rows, accepted_len, rejected, out_token, status=None, seed=0, step=0,
-                      session_base=0):
+                      session_base=0, step_counter=None):
     """dssd_device_batch: the device side's view (Q rows, received P rows and j)."""
     import torch
     assert p_rows.is_contiguous() and p_rows.dtype in (torch.float32, torch.float16)
@@ -224,12 +226,13 @@ def make_device_batch(inputs, p_rows, accepted_len, rejected, out_token, status=
                              draft_probs=_dp(inputs["draft_probs"]), p_rows=_dp(p_rows),
                              accepted_len=_dp(accepted_len), rejected=_dp(rejected), seed=seed, step=step,
                              session_base=session_base, reserved=0, out_token=_dp(out_token),
-                             status=_dp(status))
+                             status=_dp(status), step_counter=_dp(step_counter))
 
 
-def make_batch(inputs, seed=0, step=0, session_base=0, q_scalars=None, flags=0):
+def make_batch(inputs, seed=0, step=0, session_base=0, q_scalars=None, flags=0, step_counter=None):
     """dssd_batch from a dict of device tensors as `synth.generate` returns them.  With
-    `q_scalars` ([R_Q] fp32) the batch carries those instead of the Q rows (the edge's view)."""
+    `q_scalars` ([R_Q] fp32) the batch carries those instead of the Q rows (the edge's view).
+    `step_counter`: a one-element int64 device tensor the kernels add to `step` when they run."""
     import torch
     lg = inputs["logits"]
     assert lg.is_contiguous() and inputs["draft_probs"].is_contiguous()
@@ -245,7 +248,7 @@ def make_batch(inputs, seed=0, step=0, session_base=0, q_scalars=None, flags=0):
                       draft_probs=None if q_scalars is not None else _dp(inputs["draft_probs"]),
                       draft_tokens=_dp(inputs["draft_tokens"]),
                       inv_temperature=_dp(it), seed=seed, step=step, session_base=session_base, flags=flags,
-                      draft_q_tok=_dp(q_scalars))
+                      draft_q_tok=_dp(q_scalars), step_counter=_dp(step_counter))
 
 
 def alloc_out(inputs, device, debug=True):

@@ -143,7 +143,8 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   auto mis = [](const void* p, uintptr_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) != 0; };
   if (mis(b->logits, esz) || mis(b->draft_probs, 4) || mis(b->draft_q_tok, 4) || mis(b->draft_tokens, 4) || mis(b->draft_offsets, 4) ||
       mis(b->inv_temperature, 4) || mis(o->accepted_len, 4) || mis(o->rejected, 4) || mis(o->out_token, 4) ||
-      mis(o->row_stats, 4) || mis(o->p_tok, 4) || mis(o->q_tok, 4) || mis(o->status, 4))
+      mis(o->row_stats, 4) || mis(o->p_tok, 4) || mis(o->q_tok, 4) || mis(o->status, 4) ||
+      mis(b->step_counter, 8))
     return DSSD_EALIGN;
   const int64_t R_L = b->total_drafts + b->B;
   const int32_t C = chunks_per_row(b->V, b->logits_dtype);
@@ -155,6 +156,7 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   v->tokens = b->draft_tokens; v->inv_temp = b->inv_temperature;
   v->seed_lo = (uint32_t)b->seed; v->seed_hi = (uint32_t)(b->seed >> 32);
   v->step_lo = (uint32_t)b->step; v->step_hi = (uint32_t)(b->step >> 32);
+  v->step_dev = b->step_counter;
   v->session_base = b->session_base;
   v->accepted_len = o->accepted_len; v->rejected = o->rejected; v->out_token = o->out_token;
   v->row_stats = o->row_stats; v->p_tok = o->p_tok; v->q_tok = o->q_tok; v->status = o->status;
@@ -389,7 +391,7 @@ extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_devic
   const bool f16 = b->p_dtype == DSSD_F16;
   auto mis = [](const void* p, uintptr_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) != 0; };
   if (mis(b->draft_probs, 4) || mis(b->p_rows, f16 ? 2 : 4) || mis(b->draft_offsets, 4) || mis(b->accepted_len, 4) ||
-      mis(b->rejected, 4) || mis(b->out_token, 4) || mis(b->status, 4))
+      mis(b->rejected, 4) || mis(b->out_token, 4) || mis(b->status, 4) || mis(b->step_counter, 8))
     return DSSD_EALIGN;
   DeviceView d;
   d.B = b->B; d.V = b->V; d.gamma = b->gamma; d.C = (b->V + 4095) / 4096; d.R_Q = b->total_drafts;
@@ -398,6 +400,7 @@ extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_devic
   d.accepted_len = b->accepted_len; d.rejected = b->rejected;
   d.seed_lo = (uint32_t)b->seed; d.seed_hi = (uint32_t)(b->seed >> 32);
   d.step_lo = (uint32_t)b->step; d.step_hi = (uint32_t)(b->step >> 32);
+  d.step_dev = b->step_counter;
   d.session_base = b->session_base;
   d.out_token = b->out_token; d.status = b->status; d.resid_mass = c->resid_mass;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);

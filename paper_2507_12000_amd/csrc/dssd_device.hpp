@@ -44,6 +44,16 @@ struct Philox {
     w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
   }
 };
+// The block of (session, position) at the launch's step.  The step is the host's value plus,
+// when step_dev is given, a 64-bit counter in device memory read at run time: a captured graph
+// then draws fresh numbers on every replay if the caller bumps the counter between replays.
+__device__ __forceinline__ Philox step_block(uint32_t session, uint32_t position, uint32_t step_lo,
+                                             uint32_t step_hi, const uint64_t* step_dev, uint32_t seed_lo,
+                                             uint32_t seed_hi) {
+  uint64_t step = ((uint64_t)step_hi << 32) | step_lo;
+  if (step_dev) step += *step_dev;
+  return Philox(session, position, (uint32_t)step, (uint32_t)(step >> 32), seed_lo, seed_hi);
+}
 // top 24 bits -> [0,1), exact in fp32
 __device__ __forceinline__ float u01(uint32_t word) { return (float)(word >> 8) * 5.9604644775390625e-8f; }
 

@@ -33,6 +33,7 @@ struct BatchView {
   const int32_t* tokens;
   const float* inv_temp;             // may be null
   uint32_t seed_lo, seed_hi, step_lo, step_hi, session_base;
+  const uint64_t* step_dev;          // may be null: device-resident counter added to the step
   // outputs
   int32_t* accepted_len;
   int32_t* rejected;
@@ -264,8 +265,8 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out) {
               const float zx = load_logit(logits_row<BF16>(a, lrow), x, BF16);
               p = fast_exp2(fmaf(zx, c1, -st.x)) / st.y;
               q = a.q_scalars ? a.q_scalars[qrow] : a.draft_probs[qrow * (int64_t)a.V + x];
-              const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)i, a.step_lo, a.step_hi, a.seed_lo,
-                               a.seed_hi);
+              const Philox rnd = step_block(a.session_base + (uint32_t)b, (uint32_t)i, a.step_lo, a.step_hi, a.step_dev,
+                                      a.seed_lo, a.seed_hi);
               const float r = u01(rnd.w[0]);
               reject = !(__fmul_rn(r, q) < p);
             }
@@ -529,7 +530,8 @@ __device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, 
   const float invZ = 1.f / st.y;
   const char* lp = logits_row<BF16>(a, lrow);
   const float* qp = RESID ? a.draft_probs + (lrow - b) * (int64_t)a.V : nullptr;
-  const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)n, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi);
+  const Philox rnd = step_block(a.session_base + (uint32_t)b, (uint32_t)n, a.step_lo, a.step_hi, a.step_dev,
+                                      a.seed_lo, a.seed_hi);
   const float r = u01(rnd.w[RESID ? 1 : 2]);
 
   const float2* cs = a.chunk_stats + lrow * a.C;
@@ -632,7 +634,8 @@ __global__ __launch_bounds__(256) void pick_sparse(const BatchView a) {
   }
   const int32_t idx_r = __builtin_amdgcn_ds_permute(rank * 4, idx);
   const float w_r = __builtin_bit_cast(float, __builtin_amdgcn_ds_permute(rank * 4, __builtin_bit_cast(int, w)));
-  const Philox rnd(a.session_base + (uint32_t)b, (uint32_t)n, a.step_lo, a.step_hi, a.seed_lo, a.seed_hi);
+  const Philox rnd = step_block(a.session_base + (uint32_t)b, (uint32_t)n, a.step_lo, a.step_hi, a.step_dev,
+                                      a.seed_lo, a.seed_hi);
   const float r = u01(rnd.w[RESID ? 1 : 2]);
   int32_t token = draw_from_ranked(w_r, idx_r, r, lane);
   bool from_p = false;

@@ -87,6 +87,7 @@ struct DeviceView {
   const int32_t* accepted_len;       // [B] received j - 1
   const int32_t* rejected;           // [B]
   uint32_t seed_lo, seed_hi, step_lo, step_hi, session_base;
+  const uint64_t* step_dev;          // may be null: device-resident counter added to the step
   int32_t* out_token;                // [B]
   int32_t* status;                   // may be null
   float* resid_mass;                 // workspace [B, C]
@@ -203,7 +204,8 @@ __global__ __launch_bounds__(256) void device_pick(const DeviceView d) {
   if (!device_session(d, b, &qrow, &n, lane == 0)) return;
   const char* pp = static_cast<const char*>(d.p_rows) + (int64_t)b * d.V * (PF16 ? 2 : 4);
   const float* qp = d.draft_probs + qrow * (int64_t)d.V;
-  const Philox rnd(d.session_base + (uint32_t)b, (uint32_t)n, d.step_lo, d.step_hi, d.seed_lo, d.seed_hi);
+  const Philox rnd = step_block(d.session_base + (uint32_t)b, (uint32_t)n, d.step_lo, d.step_hi, d.step_dev,
+                                d.seed_lo, d.seed_hi);
   const float r = u01(rnd.w[1]);
   float* rm = d.resid_mass + (int64_t)b * d.C;
   float target = 0.f, total = 0.f;

@@ -334,6 +334,55 @@ def test_step_inside_a_hip_graph(ctx):
         assert other["out_token"].shape == eager["out_token"].shape
 
 
+def test_graph_replays_draw_fresh_numbers_through_the_step_counter(ctx):
+    """`step` is frozen into a captured graph; the device-resident step counter is not.  A graph
+    that runs the step and then bumps the counter reproduces, replay by replay, what eager calls
+    give at step + 0, + 1, + 2, ...; and a counter in eager mode equals the same host-side step."""
+    w = synth.Workload("graph_counter", B=48, V=30000, gamma=5, dtype="bf16", sigmas=(0.5, 1.5),
+                       frac_q_equals_p=0.2)
+    inputs = synth.generate(w, seed=17, device=DEV)
+    base = (1 << 32) - 2                          # the sum crosses the low word
+    counter = torch.zeros(1, dtype=torch.int64, device=DEV)
+    batch = D.make_batch(inputs, seed=9, step=base, step_counter=counter)
+    t, out = D.alloc_out(inputs, DEV)
+    counter.fill_(3)
+    ctx.step_fused(batch, out)                    # eager, counter = 3
+    torch.cuda.synchronize()
+    want = gpu_step(ctx, inputs, 9, base + 3)
+    for k in want:
+        assert (t[k].cpu().numpy() == want[k]).all(), k
+    counter.zero_()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        ctx.step(batch, out)                      # warm-up on the capture stream
+        counter.add_(1)
+        torch.cuda.synchronize()
+        counter.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            ctx.step(batch, out)
+            counter.add_(1)
+    torch.cuda.synchronize()
+    seen = []
+    for rep in range(4):
+        for v in t.values():
+            v.fill_(-3)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {k: v.cpu().numpy().copy() for k, v in t.items()}
+        want = gpu_step(ctx, inputs, 9, base + rep)          # eager work between replays
+        for k in want:
+            assert (got[k] == want[k]).all(), (k, rep)
+        seen.append(got["out_token"])
+    assert int(counter.item()) == 4
+    assert any((seen[0] != s).any() for s in seen[1:])       # the replays really differ
+    bad = D.make_batch(inputs, seed=9, step=0, step_counter=counter)
+    bad.step_counter += 4                                    # not 8-byte aligned
+    assert D.dssd_verify_batch(ctx.handle, bad, out, ctx.stream(), check=False) == D.DSSD_EALIGN
+
+
 def test_non_finite_logits_are_flagged_not_followed(ctx):
     """A NaN or +inf logit poisons its row's softmax: the session is reported (BAD_ROW) and
     skipped by the samplers; its neighbours are untouched."""
