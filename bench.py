@@ -115,6 +115,44 @@ def cpu_baseline(inputs, seed, budget_s=12.0):
     return out
 
 
+def time_graph_replays(ctx, D, torch, run, batch, out, inputs, w, args):
+    """One step recorded into a HIP graph together with the increment of the step counter the
+    kernels read at run time, then replayed: what a serving loop that cannot afford per-launch
+    host work would do.  The increment is a launch of its own and is inside the timed region."""
+    dev = inputs["logits"].device
+    counter = torch.zeros(1, dtype=torch.int64, device=dev)
+    batch.step = 0
+    batch.step_counter = counter.data_ptr()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        run(batch, out)
+        counter.add_(1)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run(batch, out)
+            counter.add_(1)
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    assert int(counter.item()) == 1 + args.warmup + args.steps
+    return {"metric": "verified_draft_positions_per_sec", "value": inputs["R_Q"] * args.steps / el,
+            "unit": "positions/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": 1e3 * el / args.steps, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": w.name, "entry": "dssd_step_fused" if args.fused else
+                       "dssd_verify_batch+dssd_residual_sample+dssd_bonus_sample",
+                       "mode": "hip graph replay, step counter in device memory"},
+            "roofline": None, "cpu_baseline": None}
+
+
 def time_split_path(ctx, D, torch, inputs, outs, args):
     """The same batch through the paper's split: the edge verifies from the uploaded scalars
     q_i(x_i) and draws bonus tokens, exports P_n of every rejected session as fp16 (the downlink
@@ -177,6 +215,9 @@ def main():
                     help="run the step through dssd_step_fused (one launch where the batch allows it)")
     ap.add_argument("--fused-limit", type=int, default=None,
                     help="largest grid (workgroups) dssd_step_fused runs as one launch (library default 512)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step (plus the bump of a device-resident step counter) into a HIP "
+                         "graph and time its replays; prints a reduced line (no per-kernel events)")
     ap.add_argument("--fused-pair-limit", type=int, default=None,
                     help="largest grid dssd_step_fused runs as two launches (library default 512)")
     ap.add_argument("--top-k", type=int, default=0,
@@ -250,6 +291,10 @@ def main():
         D.dssd_set_fused_limit(ctx.handle, args.fused_limit)
     if args.fused_pair_limit is not None:
         D.dssd_set_fused_pair_limit(ctx.handle, args.fused_pair_limit)
+    if args.graph:
+        print(json.dumps(time_graph_replays(ctx, D, torch, run, batch, out, inputs, w, args)))
+        ctx.close()
+        return
     for k in range(args.warmup):
         batch.step = k
         step_fn(batch, out)
