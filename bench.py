@@ -215,6 +215,9 @@ def main():
                     help="run the step through dssd_step_fused (one launch where the batch allows it)")
     ap.add_argument("--fused-limit", type=int, default=None,
                     help="largest grid (workgroups) dssd_step_fused runs as one launch (library default 512)")
+    ap.add_argument("--early-exit", action="store_true",
+                    help="DSSD_FLAG_EARLY_EXIT: read each session's rows only up to its first rejection "
+                         "(a mode beside the headline, which reads every row)")
     ap.add_argument("--graph", action="store_true",
                     help="record one step (plus the bump of a device-resident step counter) into a HIP "
                          "graph and time its replays; prints a reduced line (no per-kernel events)")
@@ -268,6 +271,8 @@ def main():
     if args.top_k > 0:
         w = synth.scaled(w, top_k=args.top_k, name=f"{w.name}_top{args.top_k}")
         flags = 0 if args.top_k_dense else D.FLAG_SPARSE_SUPPORT
+    if args.early_exit:
+        flags |= D.FLAG_EARLY_EXIT
     inputs = synth.generate(w, seed=args.seed, device=dev)
     torch.cuda.synchronize()
     ctx = D.Context(dev, max_rows=inputs["R_L"], max_V=w.V)
@@ -309,8 +314,8 @@ def main():
 
     # Timed region.  Only the dominant kernel is bracketed by HIP events here (every bracket
     # costs queue time; with all kernels bracketed a 15 us step reads as 47 us).
-    dom_id = D.K_ROW_STATS
-    if args.fused:   # which kernel does this batch run as?  one untimed probe step tells
+    dom_id = D.K_ROW_STATS_BLOCK if args.early_exit else D.K_ROW_STATS
+    if args.fused and not args.early_exit:   # which kernel does this batch run as?  one untimed probe step tells
         D.dssd_profile_reset(ctx.handle)
         D.dssd_profile_enable(ctx.handle, 1 << D.K_FUSED_STEP)
         step_fn(batch, out)
@@ -327,7 +332,8 @@ def main():
     elapsed = time.perf_counter() - t0
     D.dssd_profile_enable(ctx.handle, False)
     dom_ms, dom_n = D.dssd_profile_read(ctx.handle, dom_id)
-    assert dom_n == args.steps
+    assert dom_n == args.steps or (args.early_exit and dom_n % args.steps == 0)
+    dom_per_step = dom_n // args.steps     # early exit: the statistics kernel runs once per round
 
     # Per-kernel breakdown from a second, separate region with every kernel bracketed.
     D.dssd_profile_reset(ctx.handle)
@@ -346,11 +352,15 @@ def main():
     if flags & D.FLAG_SPARSE_SUPPORT:   # the samplers touch a few dozen entries per session, not rows
         ab["total"] -= ab["residual"] + ab["bonus"]
         ab["residual"] = ab["bonus"] = 0
+    if args.early_exit:   # rows 0..n_b of every session are read, nothing after the first rejection
+        visited = int((outs["accepted_len"].cpu().numpy().astype("int64") + 1).sum())
+        ab["total"] += visited * w.V * s_L - ab["row_stats"]
+        ab["row_stats"] = visited * w.V * s_L
     ms_per_step = 1e3 * elapsed / args.steps
     # dominant kernel: the row statistics, or the single fused launch when the step ran as one
     dom = D.kernel_name(dom_id)
     dom_bytes = ab["total"] if dom_id == D.K_FUSED_STEP else ab["row_stats"]
-    k1_us = 1e3 * dom_ms / dom_n
+    k1_us = 1e3 * dom_ms / dom_n * dom_per_step   # per step (all rounds together)
     achieved = dom_bytes / (k1_us * 1e-6) / 1e9
     pmc = PMC_TRAFFIC.get(w.name)
     traffic = (pmc["bytes_per_launch"] if pmc and dom == "row_chunk_stats"
@@ -366,6 +376,7 @@ def main():
         "config": {"workload": w.name, "entry": "dssd_step_fused" if args.fused else
                    "dssd_verify_batch+dssd_residual_sample+dssd_bonus_sample", "B": w.B, "V": w.V, "logits_dtype": w.dtype,
                    "input_copies_rotated": max(args.rotate, 1), "top_k": args.top_k, "sparse_support": bool(flags & D.FLAG_SPARSE_SUPPORT),
+                   "early_exit": bool(flags & D.FLAG_EARLY_EXIT),
                    "logits_rows": inputs["R_L"], "draft_positions": inputs["R_Q"],
                    "rejected_sessions": int(rejected.sum())},
         "vocab_rows_per_sec": inputs["R_L"] * args.steps / elapsed,
@@ -394,7 +405,7 @@ def main():
         ceiling = (nbytes // 8192) * 8192 / (ms / n * 1e-3) / 1e9
         result["roofline"]["measured_read_ceiling_GBps"] = ceiling
         result["roofline"]["frac_of_measured_read_ceiling"] = achieved / ceiling
-    if not args.fused:
+    if not args.fused and not args.early_exit:
         # the same step through the single whole-step call (bit-identical outputs; it folds the
         # bonus draw into the accept launch, or runs one launch for small batches): a second
         # figure beside the headline, which stays the three calls
@@ -409,6 +420,24 @@ def main():
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
         result["whole_step_call"] = {"entry": "dssd_step_fused", "ms_per_step": 1e3 * el / args.steps,
+                                     "value": inputs["R_Q"] * args.steps / el, "unit": "positions/s"}
+    if not args.fused and not args.early_exit and not flags:
+        # the same step when the caller allows rows after a session's first rejection to stay
+        # unread (DSSD_FLAG_EARLY_EXIT): same records and tokens, fewer bytes.  A figure beside
+        # the headline, which reads every row.
+        ee = D.make_batch(inputs, seed=args.seed, step=0, flags=D.FLAG_EARLY_EXIT)
+        for k in range(args.warmup):
+            ee.step = k
+            ctx.step_fused(ee, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            ee.step = args.warmup + k
+            ctx.step_fused(ee, out)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        result["early_exit_mode"] = {"entry": "dssd_step_fused + DSSD_FLAG_EARLY_EXIT",
+                                     "ms_per_step": 1e3 * el / args.steps,
                                      "value": inputs["R_Q"] * args.steps / el, "unit": "positions/s"}
     if args.split:
         result["split_path"] = time_split_path(ctx, D, torch, inputs, outs, args)

@@ -67,7 +67,18 @@ enum {
    * verify then also records each row's support while it streams the row, and the two samplers
    * draw from those few entries instead of passing over the vocabulary again.  Same results as
    * without the flag up to summation order. */
-  DSSD_FLAG_SPARSE_SUPPORT = 1
+  DSSD_FLAG_SPARSE_SUPPORT = 1,
+  /* Early exit: the caller allows the library to take the loop of Algorithm 2 ("while j <=
+   * gamma and Flag = 1") at its word and read a session's logits rows only about as far as its
+   * first rejected draft.  The rows are visited in rounds of growing blocks (by default [0,2),
+   * [2,6), the rest; fewer rounds for smaller batches, none where the extra launches would cost
+   * more than they save), and a session leaves as soon as a block holds its first rejection or
+   * its bonus row.  accepted_len, rejected and out_token are bit-identical to the default path,
+   * and so are row_stats, p_tok and q_tok for the rows and positions of the blocks that were
+   * visited; entries of later blocks are NaN, and a fault (bad token, non-finite row) there
+   * goes unnoticed.  Honoured by dssd_verify_batch and dssd_step_fused; not combinable with
+   * DSSD_FLAG_SPARSE_SUPPORT (DSSD_EUNSUPPORTED). */
+  DSSD_FLAG_EARLY_EXIT = 2
 };
 #define DSSD_MAX_SUPPORT 64
 
@@ -168,6 +179,10 @@ dssd_status dssd_step_fused(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *ou
  * as a single launch; 0 disables the single-launch path; a negative value sets the limit to its
  * magnitude and lifts the row-length rule (for tests and measurements). */
 dssd_status dssd_set_fused_limit(dssd_ctx *ctx, int64_t max_blocks);
+/* Blocks of DSSD_FLAG_EARLY_EXIT: begin[0..n) are the first rows of the blocks, strictly
+ * increasing from begin[0] = 0, the last block open-ended; n in [2, 8] (one block would be the
+ * default path).  n = 0 returns to the automatic choice by batch size. */
+dssd_status dssd_set_early_exit_schedule(dssd_ctx *ctx, const int32_t *begin, int32_t n);
 /* Largest grid that dssd_step_fused runs as two launches when the single-launch rule does not
  * apply; 0 disables the two-launch path.  Negative values are DSSD_EINVAL. */
 dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
@@ -216,7 +231,7 @@ const char *dssd_status_str(dssd_status s);
  * the device-side redraw, 8 the single-launch step of dssd_step_fused, 9 the read probe. */
 enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
        DSSD_K_BONUS_PICK = 4, DSSD_K_EXPORT_P = 5, DSSD_K_DEVICE_MASS = 6, DSSD_K_DEVICE_PICK = 7,
-       DSSD_K_FUSED_STEP = 8, DSSD_K_READ_PROBE = 9, DSSD_K_COUNT = 10 };
+       DSSD_K_FUSED_STEP = 8, DSSD_K_READ_PROBE = 9, DSSD_K_ROW_STATS_BLOCK = 10, DSSD_K_COUNT = 11 };
 dssd_status dssd_profile_enable(dssd_ctx *ctx, uint32_t kernel_mask);
 /* Synchronises the recorded events, returns the summed duration (ms) and number of launches
  * of one kernel since the last reset. */

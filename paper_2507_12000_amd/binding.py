@@ -14,14 +14,15 @@ DSSD_OK, DSSD_EINVAL, DSSD_EALIGN, DSSD_ENOMEM, DSSD_EHIP, DSSD_EUNSUPPORTED = 0
 SESSION_BAD_TOKEN, SESSION_ZERO_RESIDUAL, SESSION_BAD_OFFSETS, SESSION_BAD_ROW = 1, 2, 4, 8
 SESSION_SUPPORT_OVERFLOW = 16
 FLAG_SPARSE_SUPPORT = 1
+FLAG_EARLY_EXIT = 2
 MAX_SUPPORT = 64
 K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
-K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_COUNT = 5, 6, 7, 8, 9, 10
+K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_ROW_STATS_BLOCK, K_COUNT = 5, 6, 7, 8, 9, 10, 11
 
 # every symbol include/dssd.h declares
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
-           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_random_words", "dssd_status_str", "dssd_profile_enable",
+           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_status_str", "dssd_profile_enable",
            "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name", "dssd_probe_read")
 
 
@@ -83,6 +84,8 @@ def load():
     L.dssd_set_fused_limit.restype = C.c_int
     L.dssd_random_words.argtypes = [P, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32, P, P]
     L.dssd_random_words.restype = C.c_int
+    L.dssd_set_early_exit_schedule.argtypes = [P, C.POINTER(C.c_int32), C.c_int32]
+    L.dssd_set_early_exit_schedule.restype = C.c_int
     L.dssd_set_fused_pair_limit.argtypes = [P, C.c_int64]
     L.dssd_set_fused_pair_limit.restype = C.c_int
     for name in ("dssd_verify_batch", "dssd_residual_sample", "dssd_bonus_sample", "dssd_step_fused"):
@@ -164,6 +167,12 @@ def dssd_set_fused_limit(ctx, max_blocks):
 def dssd_random_words(ctx, seed, step, session_first, position_first, n_sessions, n_positions, words_ptr, stream):
     return load().dssd_random_words(ctx, seed, step, session_first, position_first, n_sessions, n_positions,
                                     words_ptr, stream)
+
+
+def dssd_set_early_exit_schedule(ctx, begin):
+    """begin: first rows of the blocks, e.g. (0, 2, 6); () returns to the automatic choice."""
+    arr = (C.c_int32 * max(len(begin), 1))(*begin)
+    return load().dssd_set_early_exit_schedule(ctx, arr, len(begin))
 
 
 def dssd_set_fused_pair_limit(ctx, max_blocks):

@@ -4,11 +4,13 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
 #include "dssd_fused_kernels.hpp"
 #include "dssd_util_kernels.hpp"
+#include "dssd_lazy_kernels.hpp"
 #include "dssd_split_kernels.hpp"
 
 using namespace dssd;
@@ -28,6 +30,11 @@ struct dssd_ctx {
   Job* bonus_job = nullptr;
   int32_t* arrive_resid = nullptr;
   int32_t* arrive_stats = nullptr;
+  int32_t* open_list[2] = {nullptr, nullptr};   // early exit: sessions open in odd / even rounds
+  RowTask* open_rows[2] = {nullptr, nullptr};   // and the rows such a round takes statistics of
+  int32_t ee_begin[kMaxRounds] = {0};           // early-exit schedule set by the caller (ee_rounds > 0)
+  int ee_rounds = 0;
+  int32_t* open_count = nullptr;                // [2 * kMaxRounds]: list lengths per round (sessions, then rows)
   int32_t* support_count = nullptr;
   int32_t* support_idx = nullptr;
   float* support_z = nullptr;
@@ -52,7 +59,7 @@ extern "C" size_t dssd_workspace_bytes(int64_t max_rows, int32_t max_V, int32_t 
   return align256(rows * C * sizeof(float2)) + align256(rows * sizeof(float2)) +
          align256(rows * C * sizeof(float)) + 2 * align256(rows * sizeof(Job)) +
          align256(2 * rows * sizeof(int32_t)) + align256(rows * sizeof(int32_t)) +
-         2 * align256(rows * kMaxSupport * sizeof(int32_t));
+         2 * align256(rows * kMaxSupport * sizeof(int32_t)) + 2 * align256(rows * sizeof(int32_t)) + 2 * align256(rows * sizeof(RowTask)) + 256;
 }
 
 extern "C" const char* dssd_status_str(dssd_status s) {
@@ -70,7 +77,8 @@ extern "C" const char* dssd_status_str(dssd_status s) {
 extern "C" const char* dssd_kernel_name(int k) {
   static const char* names[DSSD_K_COUNT] = {"row_chunk_stats", "accept_scan", "resid_mass", "resid_pick",
                                             "bonus_pick", "export_p_rows", "device_resid_mass",
-                                            "device_resid_pick", "fused_small_step", "read_probe"};
+                                            "device_resid_pick", "fused_small_step", "read_probe",
+                                            "row_chunk_stats_block"};
   return (k >= 0 && k < DSSD_K_COUNT) ? names[k] : "?";
 }
 
@@ -103,7 +111,12 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   c->arrive_stats = c->arrive_resid + rows;           p += align256(2 * rows * sizeof(int32_t));
   c->support_count = reinterpret_cast<int32_t*>(p);   p += align256(rows * sizeof(int32_t));
   c->support_idx = reinterpret_cast<int32_t*>(p);     p += align256(rows * kMaxSupport * sizeof(int32_t));
-  c->support_z = reinterpret_cast<float*>(p);
+  c->support_z = reinterpret_cast<float*>(p);         p += align256(rows * kMaxSupport * sizeof(float));
+  c->open_list[0] = reinterpret_cast<int32_t*>(p);    p += align256(rows * sizeof(int32_t));
+  c->open_list[1] = reinterpret_cast<int32_t*>(p);    p += align256(rows * sizeof(int32_t));
+  c->open_rows[0] = reinterpret_cast<RowTask*>(p);    p += align256(rows * sizeof(RowTask));
+  c->open_rows[1] = reinterpret_cast<RowTask*>(p);    p += align256(rows * sizeof(RowTask));
+  c->open_count = reinterpret_cast<int32_t*>(p);
   // arrival counters start at zero; every kernel that uses them leaves them at zero
   if (hipMemset(c->arrive_resid, 0, 2 * rows * sizeof(int32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
     (void)hipFree(c->workspace);
@@ -132,7 +145,8 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   if (!c || !b || !o) return DSSD_EINVAL;
   if (b->B < 0 || b->V < 1 || b->gamma < 0 || b->total_drafts < 0) return DSSD_EINVAL;
   if (b->logits_dtype != DSSD_F32 && b->logits_dtype != DSSD_BF16) return DSSD_EINVAL;
-  if (b->flags & ~(uint32_t)DSSD_FLAG_SPARSE_SUPPORT) return DSSD_EINVAL;
+  if (b->flags & ~(uint32_t)(DSSD_FLAG_SPARSE_SUPPORT | DSSD_FLAG_EARLY_EXIT)) return DSSD_EINVAL;
+  if ((b->flags & DSSD_FLAG_SPARSE_SUPPORT) && (b->flags & DSSD_FLAG_EARLY_EXIT)) return DSSD_EUNSUPPORTED;
   if (!b->draft_offsets && b->total_drafts != (int64_t)b->B * b->gamma) return DSSD_EINVAL;
   if (b->B > 0) {
     if (!b->logits) return DSSD_EINVAL;
@@ -199,6 +213,81 @@ struct Timed {
 
 static dssd_status launch_status() { return hipGetLastError() == hipSuccess ? DSSD_OK : DSSD_EHIP; }
 
+// Early exit: rounds of (chunk statistics of a block of rows, accept scan of that block) over the
+// sessions that are still open.  `begin` holds the first row of every block; the last block is
+// open-ended.  Blocks grow because the share of open sessions shrinks geometrically while every
+// round costs two launches.  Measured on the benchmark workloads: three rounds {0,2,6} are best
+// from a few GB of logits on, two rounds {0,3} below that, and under about a quarter of a GB the
+// extra launches cost more than the rows they save (the default path runs instead).
+struct Schedule { int32_t begin[kMaxRounds]; int n; };
+static Schedule early_exit_schedule(const dssd_ctx* c, const dssd_batch* b, const BatchView& v) {
+  if (c->ee_rounds > 0) {
+    Schedule s{}; s.n = c->ee_rounds;
+    for (int r = 0; r < s.n; ++r) s.begin[r] = c->ee_begin[r];
+    return s;
+  }
+  const double bytes = (double)v.R_L * b->V * (b->logits_dtype == DSSD_BF16 ? 2 : 4);
+  if (bytes < 256e6) return Schedule{{0}, 0};   // not worth it
+  if (bytes < 1.5e9) return Schedule{{0, 3}, 2};
+  return Schedule{{0, 2, 6}, 3};
+}
+
+static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const BatchView& v, hipStream_t s,
+                                       bool tail_bonus, const Schedule& sched) {
+  const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  const int32_t* kEarlyExitBegin = sched.begin;
+  const int kEarlyExitRounds = sched.n;
+  const int32_t known_rows = b->draft_offsets ? 0x7FFFFFFF : b->gamma + 1;   // rows per session, if uniform
+  int32_t* n_sessions = c->open_count;              // [kMaxRounds] sessions listed for round r
+  int32_t* n_rows = c->open_count + kMaxRounds;     // [kMaxRounds] rows listed for round r
+  for (int r = 0; r < kEarlyExitRounds; ++r) {
+    const int32_t begin = kEarlyExitBegin[r];
+    if (begin >= known_rows) break;
+    const bool last = r == kEarlyExitRounds - 1 || kEarlyExitBegin[r + 1] >= known_rows;
+    const int32_t end = last ? 0x7FFFFFFF : kEarlyExitBegin[r + 1];
+    {
+      Timed t(c, DSSD_K_ROW_STATS_BLOCK, s);
+      if (r == 0) {
+        const int32_t w = std::min(end, known_rows);
+        const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
+        if (blocks > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+#define DSSD_HEAD(BF, AL) DSSD_LAUNCH((row_chunk_stats_head<BF, AL>), blocks, s, v, w, c->open_count, 2 * kMaxRounds)
+        if (bf16) { if (al) DSSD_HEAD(true, true); else DSSD_HEAD(true, false); }
+        else      { if (al) DSSD_HEAD(false, true); else DSSD_HEAD(false, false); }
+#undef DSSD_HEAD
+      } else {
+        // the rows listed by the accept launch before: at most every row that is left
+        const int64_t rows_left = b->draft_offsets ? v.R_L : (int64_t)b->B * (known_rows - begin);
+        const int64_t worst = last ? rows_left : std::min<int64_t>(rows_left, (int64_t)b->B * (end - begin));
+        const int64_t blocks = (std::min<int64_t>((worst * v.C + 3) / 4, 1 << 16) + 7) / 8 * 8;
+        const RowTask* rows = c->open_rows[r & 1];
+#define DSSD_LIST(BF, AL) DSSD_LAUNCH((row_chunk_stats_list<BF, AL>), blocks, s, v, rows, n_rows + r)
+        if (bf16) { if (al) DSSD_LIST(true, true); else DSSD_LIST(true, false); }
+        else      { if (al) DSSD_LIST(false, true); else DSSD_LIST(false, false); }
+#undef DSSD_LIST
+      }
+    }
+    {
+      Timed t(c, DSSD_K_ACCEPT, s);
+      const OpenSessions open{r ? c->open_list[r & 1] : nullptr, r ? n_sessions + r : nullptr};
+      int32_t* next_list = last ? nullptr : c->open_list[(r + 1) & 1];
+      int32_t* next_count = last ? nullptr : n_sessions + r + 1;
+      RowTask* next_rows = last ? nullptr : c->open_rows[(r + 1) & 1];
+      int32_t* next_n_rows = last ? nullptr : n_rows + r + 1;
+      // the round after next starts at begin[r + 2]: the next one takes the rows in between, or all
+      const int32_t next_width = last ? 0 : (r + 2 < kEarlyExitRounds ? kEarlyExitBegin[r + 2] - end : 0x7FFFFFFF);
+#define DSSD_ACC(BF, AL) do { \
+        if (tail_bonus) DSSD_LAUNCH((accept_scan_block<BF, AL, true>), b->B, s, v, open, begin, end, next_list, next_count, next_rows, next_n_rows, next_width); \
+        else DSSD_LAUNCH((accept_scan_block<BF, AL, false>), b->B, s, v, open, begin, end, next_list, next_count, next_rows, next_n_rows, next_width); } while (0)
+      if (bf16) { if (al) DSSD_ACC(true, true); else DSSD_ACC(true, false); }
+      else      { if (al) DSSD_ACC(false, true); else DSSD_ACC(false, false); }
+#undef DSSD_ACC
+    }
+    if (last) break;
+  }
+  return launch_status();
+}
+
 // Row statistics, then accept / first-reject per session.  tail_bonus: the accept kernel also
 // draws the bonus token of all-accepted sessions (dense rows only).
 static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const BatchView& v, hipStream_t s,
@@ -208,6 +297,10 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
   if ((tasks + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
   const unsigned grid = (unsigned)((tasks + 3) / 4);
   const bool sparse = (b->flags & DSSD_FLAG_SPARSE_SUPPORT) != 0;
+  if (b->flags & DSSD_FLAG_EARLY_EXIT) {
+    const Schedule sched = early_exit_schedule(c, b, v);
+    if (sched.n > 0) return early_exit_launches(c, b, v, s, tail_bonus, sched);
+  }
   if (sparse)   // the rows' support lists start empty (a fill kernel, so the call stays graph-capturable)
     hipLaunchKernelGGL(zero_i32, dim3((unsigned)((v.R_L + 255) / 256)), dim3(256), 0, s, v.support_count, v.R_L);
   {
@@ -307,7 +400,7 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
   // One launch pays only while the lone workgroup that finishes a session can stream the
   // rejected row (logits + Q) quickly: small grids and rows of a few hundred KiB.
   const int64_t resid_row_bytes = (int64_t)b->V * ((b->logits_dtype == DSSD_BF16 ? 2 : 4) + 4);
-  const bool fusable = !b->draft_offsets && !(b->flags & DSSD_FLAG_SPARSE_SUPPORT);
+  const bool fusable = !b->draft_offsets && !(b->flags & (DSSD_FLAG_SPARSE_SUPPORT | DSSD_FLAG_EARLY_EXIT));
   const bool single = fusable && groups * b->B <= c->fused_max_blocks &&
                       (c->fused_force || resid_row_bytes <= (384 << 10));
   // Longer rows, still a small grid: statistics + accept + bonus in one launch, the redraw of
@@ -345,6 +438,15 @@ extern "C" dssd_status dssd_set_fused_limit(dssd_ctx* c, int64_t max_blocks) {
   if (!c) return DSSD_EINVAL;
   c->fused_force = max_blocks < 0;
   c->fused_max_blocks = max_blocks < 0 ? -max_blocks : max_blocks;
+  return DSSD_OK;
+}
+
+extern "C" dssd_status dssd_set_early_exit_schedule(dssd_ctx* c, const int32_t* begin, int32_t n) {
+  if (!c || n < 0 || n == 1 || n > kMaxRounds || (n > 0 && (!begin || begin[0] != 0))) return DSSD_EINVAL;
+  for (int r = 1; r < n; ++r)
+    if (begin[r] <= begin[r - 1]) return DSSD_EINVAL;
+  for (int r = 0; r < n; ++r) c->ee_begin[r] = begin[r];
+  c->ee_rounds = n;
   return DSSD_OK;
 }
 

@@ -197,8 +197,15 @@ __device__ __forceinline__ float2 merge_row_wave(const float2* cs, int32_t C, in
 // from the residual at job.lrow, kind 2 = bonus token from job.lrow, 0 = nothing (device-side
 // error).  Chunk pairs are read with device-coherent loads, so the caller may be the launch that
 // produced them.
+//
+// [row_begin, row_end) restricts the call to those rows of the session (positions before
+// row_begin are known to be accepted; statistics exist for the rows in the range only).  If the
+// range holds neither a rejection nor the bonus row the session is left open: nothing is
+// written and kind 3 is returned.  With partial = true a session that is closed here gets NaN
+// in the row_stats / p_tok / q_tok entries of the rows and positions from row_end on.
 template <bool BF16>
-__device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out) {
+__device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, int32_t row_begin = 0,
+                                  int32_t row_end = 0x7FFFFFFF, bool partial = false) {
   __shared__ float2 row_st[kWave + 1];
   __shared__ Job sh_job;
   __shared__ int32_t sh_kind;
@@ -217,10 +224,11 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out) {
   const float c1 = tau * kLog2e;
   int32_t first_reject = g;
   float2 sel_st = make_float2(0.f, 0.f);   // statistics of the row the session will draw from
+  const int32_t hi = min(row_end, g + 1);   // rows [row_begin, hi) are examined here
   if (!(bad & 4)) {
-    for (int32_t base = 0; base <= g; base += kWave) {
+    for (int32_t base = row_begin; base < hi; base += kWave) {
       // rows base .. base+nrows-1 of the session (the last pass includes the bonus row)
-      const int32_t nrows = min(kWave, g + 1 - base);
+      const int32_t nrows = min(kWave, hi - base);
       for (int32_t r0 = wave; r0 < nrows; r0 += 16) {
         float2 first[4];
 #pragma unroll
@@ -288,23 +296,40 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out) {
       __syncthreads();
     }
   }
-  if (threadIdx.x == 0) {
-    if (bad) {
-      a.accepted_len[b] = 0;
-      a.rejected[b] = 1;
-      a.out_token[b] = -1;
-    } else {
-      a.accepted_len[b] = first_reject;
-      a.rejected[b] = first_reject < g ? 1 : 0;
+  if (wave == 0) {
+    const bool open = !bad && first_reject == g && hi <= g;   // no rejection yet, bonus row not reached
+    if (partial && !open && !(bad & 4)) {
+      const float nan = __builtin_nanf("");
+      if (a.row_stats)
+        for (int32_t j = hi + lane; j <= g; j += kWave) {
+          a.row_stats[2 * (lrow0 + j)] = nan;
+          a.row_stats[2 * (lrow0 + j) + 1] = nan;
+        }
+      for (int32_t j = hi + lane; j < g; j += kWave) {
+        if (a.p_tok) a.p_tok[off0 + j] = nan;
+        if (a.q_tok) a.q_tok[off0 + j] = nan;
+      }
     }
-    Job none, job;
-    none.lrow = -1; none.M2 = 0.f; none.Z = 0.f;
-    job.lrow = lrow0 + first_reject; job.M2 = sel_st.x; job.Z = sel_st.y;
-    a.resid_job[b] = (!bad && first_reject < g) ? job : none;
-    a.bonus_job[b] = (!bad && first_reject == g) ? job : none;
-    if (a.status) a.status[b] = bad;
-    sh_job = job;
-    sh_kind = bad ? 0 : (first_reject < g ? 1 : 2);
+    if (lane == 0) {
+      Job none, job;
+      none.lrow = -1; none.M2 = 0.f; none.Z = 0.f;
+      job.lrow = lrow0 + first_reject; job.M2 = sel_st.x; job.Z = sel_st.y;
+      if (!open) {
+        if (bad) {
+          a.accepted_len[b] = 0;
+          a.rejected[b] = 1;
+          a.out_token[b] = -1;
+        } else {
+          a.accepted_len[b] = first_reject;
+          a.rejected[b] = first_reject < g ? 1 : 0;
+        }
+        a.resid_job[b] = (!bad && first_reject < g) ? job : none;
+        a.bonus_job[b] = (!bad && first_reject == g) ? job : none;
+        if (a.status) a.status[b] = bad;
+      }
+      sh_job = job;
+      sh_kind = open ? 3 : (bad ? 0 : (first_reject < g ? 1 : 2));
+    }
   }
   __syncthreads();
   *job_out = sh_job;

@@ -1,0 +1,114 @@
+// Early-exit verification: the loop of Algorithm 2 ("while j <= gamma and Flag = 1") taken at its
+// word.  Row i of a session decides position i, and nothing after the first rejection is ever
+// looked at, so the rows are visited in a few rounds of growing blocks -- rows [0,k1) of every
+// session, then rows [k1,k2) of the sessions still without a rejection, and so on -- and a
+// session leaves as soon as one of its blocks holds a rejection or its bonus row.  On the
+// benchmark workloads this reads a little over half of the logits.
+//
+// Each round is the streaming pair again (chunk statistics, then one workgroup per session for
+// the accept scan), restricted to the block and to the sessions still open, which the accept
+// launch of the round before has appended to a list.  Every value that is computed is computed
+// by the same device functions in the same order as in the default path, so accepted_len,
+// rejected, out_token and the statistics of visited rows are bit-identical to its results.
+// Nothing waits on another workgroup; every launch has a grid fixed by the host and workgroups
+// without work exit at once.
+#pragma once
+#include "dssd_kernels.hpp"
+
+namespace dssd {
+
+constexpr int kMaxRounds = 8;
+
+// Sessions of a round: all of them (list == nullptr) or the `*count` entries of `list`.
+struct OpenSessions {
+  const int32_t* list;
+  const int32_t* count;
+};
+// One logits row to take statistics of, with its session's log2(e)/T.
+struct __attribute__((aligned(16))) RowTask {
+  int64_t lrow;
+  float c1;
+  int32_t pad;
+};
+
+// Round 0: chunk statistics of rows [0, width) of every session, one wave per chunk.
+// zero[0..n_zero) is cleared by the first threads (the list counters of the rounds that follow).
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, int32_t width, int32_t* zero,
+                                                            int32_t n_zero) {
+  const int lane = threadIdx.x & 63;
+  if (blockIdx.x == 0 && threadIdx.x < n_zero) zero[threadIdx.x] = 0;
+  const int64_t per_session = (int64_t)width * a.C;
+  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
+  if (task >= a.B * per_session) return;
+  const int32_t b = (int32_t)(task / per_session);
+  const int32_t rem = (int32_t)(task - b * per_session);
+  const int32_t i = rem / a.C, c = rem - i * a.C;
+  const int64_t off0 = session_first_draft(a, b);
+  const int64_t off1 = a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma;
+  if (off0 < 0 || off1 < off0 || off1 > a.R_Q) return;   // reported by the accept launch
+  if (i > off1 - off0) return;                            // the session has fewer rows
+  const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
+  const int64_t lrow = off0 + b + i;
+  const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, lrow), c, a.V, c1, lane);
+  if (lane == 0) a.chunk_stats[lrow * a.C + c] = st;
+}
+
+// Later rounds: chunk statistics of the rows the accept launch before has listed, one wave per
+// chunk, grid-stride (the grid is fixed by the host, the list length is not known there).
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, const RowTask* rows,
+                                                            const int32_t* n_rows) {
+  const int lane = threadIdx.x & 63;
+  const int64_t total = (int64_t)*n_rows * a.C;
+  // each XCD walks one contiguous eighth of the list (the grid is a multiple of 8 workgroups)
+  const int64_t nblk = (total + 3) / 4, per = (nblk + kXcds - 1) / kXcds;
+  const int64_t first = (int64_t)(blockIdx.x % kXcds) * per;
+  for (int64_t k = blockIdx.x / kXcds; k < per; k += gridDim.x / kXcds) {
+    const int64_t task = (first + k) * 4 + (threadIdx.x >> 6);
+    if (task >= total) continue;
+    const int64_t e = task / a.C;
+    const int32_t c = (int32_t)(task - e * a.C);
+    const RowTask t = rows[e];
+    const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, t.lrow), c, a.V, t.c1, lane);
+    if (lane == 0) a.chunk_stats[t.lrow * a.C + c] = st;
+  }
+}
+
+// Accept scan of rows [row_begin, row_end) for every open session, one workgroup per session.
+// A session that stays open is appended to next_list, and its next rows -- next_width of them,
+// or all that are left -- to next_rows.  TAIL_BONUS: a session whose drafts were all accepted
+// also gets its bonus token here.
+template <bool BF16, bool ALIGNED, bool TAIL_BONUS>
+__global__ __launch_bounds__(256) void accept_scan_block(const BatchView a, OpenSessions open, int32_t row_begin,
+                                                         int32_t row_end, int32_t* next_list, int32_t* next_count,
+                                                         RowTask* next_rows, int32_t* next_n_rows,
+                                                         int32_t next_width) {
+  __shared__ int32_t sh_base;
+  if (open.list && (int32_t)blockIdx.x >= *open.count) return;
+  const int32_t b = open.list ? open.list[blockIdx.x] : (int32_t)blockIdx.x;
+  Job job;
+  const int32_t kind = accept_session<BF16>(a, b, &job, row_begin, row_end, true);
+  if (kind == 3) {
+    // still open: offsets were found consistent, and row_end <= gamma_b
+    const int64_t off0 = session_first_draft(a, b);
+    const int32_t g = (int32_t)((a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma) - off0);
+    const int32_t n = min(next_width, g + 1 - row_end);
+    if (threadIdx.x == 0) {
+      next_list[atomicAdd(next_count, 1)] = b;
+      sh_base = atomicAdd(next_n_rows, n);
+    }
+    __syncthreads();
+    const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
+    for (int32_t k = threadIdx.x; k < n; k += blockDim.x) {
+      RowTask t;
+      t.lrow = off0 + b + row_end + k; t.c1 = c1; t.pad = 0;
+      next_rows[sh_base + k] = t;
+    }
+    return;
+  }
+  if constexpr (TAIL_BONUS)
+    if (kind == 2 && threadIdx.x < kWave) pick_for_session<BF16, ALIGNED, false>(a, b, job, threadIdx.x);
+}
+
+}  // namespace dssd

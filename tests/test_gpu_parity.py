@@ -1,6 +1,8 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
 on the same seeded inputs.  Bit-exact accepted_len / rejected / out_token outside counted
 near-ties; p_i(x_i) and the row log-sum-exp within 1e-5 (fp32 logits) or 2e-3 (bf16 logits)."""
+import ctypes
+
 import numpy as np
 import pytest
 
@@ -110,6 +112,32 @@ def test_benchmark_workloads_large(ctx, idx, stride):
     if (cls == 1).any():
         assert (n[cls == 1] == gam[cls == 1]).mean() > 0.95
         assert n[cls == 2].mean() < 1.0
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_benchmark_workloads_early_exit(ctx, idx):
+    """Full-size launch with DSSD_FLAG_EARLY_EXIT in the automatic schedule bench.py times:
+    records, tokens and status equal the default path's (which the test above holds against
+    the oracle), statistics are equal wherever they are not NaN, and rows were really skipped."""
+    w = synth.WORKLOADS[idx]
+    inputs = synth.generate(w, seed=0, device=DEV)
+    ref = gpu_step(ctx, inputs, 0, 3)
+    t, out = D.alloc_out(inputs, DEV)
+    D.dssd_profile_reset(ctx.handle)
+    D.dssd_profile_enable(ctx.handle, True)
+    ctx.step_fused(D.make_batch(inputs, seed=0, step=3, flags=D.FLAG_EARLY_EXIT), out)
+    torch.cuda.synchronize()
+    D.dssd_profile_enable(ctx.handle, False)
+    assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS_BLOCK)[1] in (2, 3)
+    got = {k: v.cpu().numpy() for k, v in t.items()}
+    for k in ("accepted_len", "rejected", "out_token", "status"):
+        assert (got[k] == ref[k]).all(), k
+    for k in ("row_stats", "p_tok", "q_tok"):
+        seen = ~np.isnan(got[k])
+        assert (got[k][seen] == ref[k][seen]).all(), k
+    skipped = np.isnan(got["row_stats"][:, 0]).mean()
+    print(f"[early exit] {w.name}: {skipped:.3f} of the logits rows not read", flush=True)
+    assert 0.2 < skipped < 0.8
 
 
 def test_determinism_and_shard_independence(ctx):
@@ -451,7 +479,7 @@ def test_sparse_support_overflow_is_reported(ctx):
     torch.cuda.synchronize()
     assert (t["out_token"].cpu().numpy() == -1).all()
     assert (t["status"].cpu().numpy() & D.SESSION_SUPPORT_OVERFLOW).all()
-    bad = D.make_batch(inputs, seed=1, step=1, flags=2)
+    bad = D.make_batch(inputs, seed=1, step=1, flags=1 << 7)   # not a defined flag
     assert D.dssd_verify_batch(ctx.handle, bad, out, 0, check=False) == D.DSSD_EINVAL
 
 
@@ -571,3 +599,119 @@ def test_random_blocks_match_the_published_vectors_and_the_oracle(ctx):
     assert D.dssd_random_words(ctx.handle, 0, 0, 0, 0, -1, 1, 0, ctx.stream()) == D.DSSD_EINVAL
     assert D.dssd_random_words(ctx.handle, 0, 0, 0, 0, 1, 1, 0, ctx.stream()) == D.DSSD_EINVAL
     assert D.dssd_random_words(ctx.handle, 0, 0, 0, 0, 0, 5, 0, ctx.stream()) == D.DSSD_OK
+
+
+EARLY_EXIT_CASES = [
+    synth.Workload("ee_bf16_ragged_temp", B=41, V=20000, gamma=0, dtype="bf16", gamma_range=(0, 16),
+                   temperature_range=(0.5, 1.5), sigmas=(0.25, 2.0), frac_q_equals_p=0.2, frac_q_uniform=0.2),
+    synth.Workload("ee_f32_unaligned", B=17, V=9999, gamma=5, dtype="f32", sigmas=(0.3, 1.0), frac_q_equals_p=0.2),
+    synth.Workload("ee_bf16_many_chunks", B=6, V=262144, gamma=3, dtype="bf16", sigmas=(0.5,), frac_q_equals_p=0.3),
+    synth.Workload("ee_f32_gamma70", B=5, V=3000, gamma=70, dtype="f32", sigmas=(0.02,), frac_q_equals_p=0.4),
+    synth.Workload("ee_bf16_tiny_V", B=9, V=37, gamma=4, dtype="bf16", zipf_s=0.5),
+]
+
+
+EARLY_EXIT_SCHEDULES = [(0, 2, 6), (0, 3), (0, 1, 2, 3, 5, 8, 13, 21)]
+
+
+@pytest.mark.parametrize("sched", EARLY_EXIT_SCHEDULES, ids=["-".join(map(str, s)) for s in EARLY_EXIT_SCHEDULES])
+@pytest.mark.parametrize("fused", [False, True], ids=["three_calls", "whole_step"])
+@pytest.mark.parametrize("w", EARLY_EXIT_CASES, ids=[w.name for w in EARLY_EXIT_CASES])
+def test_early_exit_equals_the_full_path_on_what_it_visits(ctx, w, fused, sched):
+    """DSSD_FLAG_EARLY_EXIT reads a session's rows only as far as the block of rows that holds
+    its first rejection.  Records and tokens are bit-identical to the default path; statistics
+    and p/q are bit-identical in the visited blocks and NaN after them; and the whole thing
+    matches the oracle."""
+    inputs = synth.generate(w, seed=23, device=DEV)
+    off = inputs["draft_offsets"]
+    off = (np.arange(w.B + 1) * w.gamma) if off is None else off.cpu().numpy().astype(np.int64)
+    assert D.dssd_set_early_exit_schedule(ctx.handle, sched) == D.DSSD_OK
+    try:
+        _early_exit_case(ctx, w, fused, sched, inputs, off)
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
+
+
+def _early_exit_case(ctx, w, fused, sched, inputs, off):
+    for step in (0, 1):
+        ref = gpu_step(ctx, inputs, 77, step)
+        batch = D.make_batch(inputs, seed=77, step=step, flags=D.FLAG_EARLY_EXIT)
+        t, out = D.alloc_out(inputs, DEV)
+        D.dssd_profile_reset(ctx.handle)
+        D.dssd_profile_enable(ctx.handle, True)
+        (ctx.step_fused if fused else ctx.step)(batch, out)
+        torch.cuda.synchronize()
+        D.dssd_profile_enable(ctx.handle, False)
+        assert 1 <= D.dssd_profile_read(ctx.handle, D.K_ROW_STATS_BLOCK)[1] <= len(sched)
+        assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)[1] == 0
+        got = {k: v.cpu().numpy() for k, v in t.items()}
+        for k in ("accepted_len", "rejected", "out_token", "status"):
+            assert (got[k] == ref[k]).all(), (k, step)
+        assert (ref["rejected"] == 0).any() and (ref["rejected"] == 1).any()
+        for b in range(w.B):
+            q0, q1, n = int(off[b]), int(off[b + 1]), int(ref["accepted_len"][b])
+            rej = int(ref["rejected"][b])
+            seen_pos = n + 1 if rej else n              # positions whose accept test ran
+            seen_rows = n + 1                           # rows 0..n (n = gamma_b when all accepted)
+            l0 = q0 + b
+            # the block that holds row n is the last one visited
+            later = [s0 for s0 in sched if s0 > n]
+            stop = later[0] if later else q1 - q0 + 1
+            vis_rows = min(stop, q1 - q0 + 1)
+            vis_pos = min(stop, q1 - q0)
+            assert vis_rows >= seen_rows and vis_pos >= seen_pos
+            for k in ("p_tok", "q_tok"):
+                assert (got[k][q0:q0 + vis_pos] == ref[k][q0:q0 + vis_pos]).all(), (k, b)
+                assert np.isnan(got[k][q0 + vis_pos:q1]).all(), (k, b)
+            assert (got["row_stats"][l0:l0 + vis_rows] == ref["row_stats"][l0:l0 + vis_rows]).all(), b
+            assert np.isnan(got["row_stats"][l0 + vis_rows:q1 + b + 1]).all(), b
+    # against the oracle: fill what was not visited from the full path, then the usual comparison
+    filled = {k: np.where(np.isnan(got[k]), ref[k], got[k]) if got[k].dtype.kind == "f" else got[k] for k in got}
+    h = parity.to_numpy_inputs(inputs)
+    orc = parity.run_oracle(h, 77, 1, workers=8)
+    parity.compare(h, filled, orc, P_RTOL[w.dtype], seed=77, step=1)
+
+
+def test_early_exit_is_skipped_for_small_batches_by_default(ctx):
+    """Without a schedule set by the caller the library decides by batch size: a batch of a few
+    MB runs the default path (every row, no NaN)."""
+    w = synth.Workload("ee_small", B=8, V=5000, gamma=4, dtype="f32")
+    inputs = synth.generate(w, seed=2, device=DEV)
+    ref = gpu_step(ctx, inputs, 3, 0)
+    t, out = D.alloc_out(inputs, DEV)
+    D.dssd_profile_reset(ctx.handle)
+    D.dssd_profile_enable(ctx.handle, True)
+    ctx.step(D.make_batch(inputs, seed=3, step=0, flags=D.FLAG_EARLY_EXIT), out)
+    torch.cuda.synchronize()
+    D.dssd_profile_enable(ctx.handle, False)
+    assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS_BLOCK)[1] == 0
+    assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)[1] == 1
+    for k in ref:
+        assert (ref[k] == t[k].cpu().numpy()).all(), k
+    bad = (ctypes.c_int32 * 3)(0, 2, 2)
+    assert D.load().dssd_set_early_exit_schedule(ctx.handle, bad, 3) == D.DSSD_EINVAL
+    bad = (ctypes.c_int32 * 2)(1, 2)
+    assert D.load().dssd_set_early_exit_schedule(ctx.handle, bad, 2) == D.DSSD_EINVAL
+    assert D.load().dssd_set_early_exit_schedule(ctx.handle, bad, 9) == D.DSSD_EINVAL
+    assert D.dssd_set_early_exit_schedule(ctx.handle, (0,)) == D.DSSD_EINVAL
+
+
+def test_early_exit_refuses_sparse_support_and_reports_bad_sessions(ctx):
+    w = synth.Workload("ee_bad", B=4, V=5000, gamma=3, dtype="f32", sigmas=(0.05,))
+    inputs = synth.generate(w, seed=3, device=DEV)
+    D.dssd_set_early_exit_schedule(ctx.handle, (0, 2))
+    t, out = D.alloc_out(inputs, DEV)
+    both = D.make_batch(inputs, seed=1, step=0, flags=D.FLAG_EARLY_EXIT | D.FLAG_SPARSE_SUPPORT)
+    assert D.dssd_verify_batch(ctx.handle, both, out, ctx.stream(), check=False) == D.DSSD_EUNSUPPORTED
+    bad = dict(inputs)
+    bad["draft_tokens"] = inputs["draft_tokens"].clone()
+    bad["draft_tokens"][3] = w.V + 5                       # session 1, position 0
+    bad["draft_offsets"] = torch.tensor([0, 3, 6, 5, 4], dtype=torch.int32, device=DEV)   # sessions 2 and 3 broken
+    ctx.step_fused(D.make_batch(bad, seed=1, step=0, flags=D.FLAG_EARLY_EXIT), out)
+    torch.cuda.synchronize()
+    st = t["status"].cpu().numpy()
+    assert st[0] == 0 and st[1] & 1 and st[2] & 4 and st[3] & 4
+    for b in (1, 2, 3):
+        assert (int(t["accepted_len"][b]), int(t["rejected"][b]), int(t["out_token"][b])) == (0, 1, -1)
+    assert int(t["out_token"][0]) >= 0
+    D.dssd_set_early_exit_schedule(ctx.handle, ())
