@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # Valid only for the kernel sources they were taken with: reported as null once those change.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "8efa39390b174b5cdfc11862a5ffafc20d18ba55c6a5dc17e15fe9434683d350",
-        "bytes_per_launch": int((2426309.2 * 2.0 + 4776.7 * 1.0) * 1024),
+        "sources_sha256": "6eac15ab4213c4bb38360e712234c6b7b52efc319e3912c81d5cb5596ab3358d",
+        "bytes_per_launch": int((2426309.9 * 2.0 + 4776.8 * 1.0) * 1024),
     },
 }
 

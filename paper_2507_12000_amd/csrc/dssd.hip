@@ -400,7 +400,8 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
   // One launch pays only while the lone workgroup that finishes a session can stream the
   // rejected row (logits + Q) quickly: small grids and rows of a few hundred KiB.
   const int64_t resid_row_bytes = (int64_t)b->V * ((b->logits_dtype == DSSD_BF16 ? 2 : 4) + 4);
-  const bool fusable = !b->draft_offsets && !(b->flags & (DSSD_FLAG_SPARSE_SUPPORT | DSSD_FLAG_EARLY_EXIT));
+  const bool early_exit = (b->flags & DSSD_FLAG_EARLY_EXIT) && early_exit_schedule(c, b, v).n > 0;
+  const bool fusable = !b->draft_offsets && !(b->flags & DSSD_FLAG_SPARSE_SUPPORT) && !early_exit;
   const bool single = fusable && groups * b->B <= c->fused_max_blocks &&
                       (c->fused_force || resid_row_bytes <= (384 << 10));
   // Longer rows, still a small grid: statistics + accept + bonus in one launch, the redraw of

@@ -229,6 +229,18 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, i
     for (int32_t base = row_begin; base < hi; base += kWave) {
       // rows base .. base+nrows-1 of the session (the last pass includes the bonus row)
       const int32_t nrows = min(kWave, hi - base);
+      // what the accept test gathers does not depend on the statistics: asked for first, so the
+      // latency runs under the row merges (wave 0, lane = position base + lane)
+      int32_t x = 0;
+      float zx = 0.f, q = 0.f;
+      if (wave == 0 && lane < nrows && base + lane < g) {
+        const int64_t qrow = off0 + base + lane;
+        x = a.tokens[qrow];
+        if (x >= 0 && x < a.V) {
+          zx = load_logit(logits_row<BF16>(a, lrow0 + base + lane), x, BF16);
+          q = a.q_scalars ? a.q_scalars[qrow] : a.draft_probs[qrow * (int64_t)a.V + x];
+        }
+      }
       for (int32_t r0 = wave; r0 < nrows; r0 += 16) {
         float2 first[4];
 #pragma unroll
@@ -261,18 +273,14 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, i
         int32_t lane_bad = 0;
         if (lane < nrows) {
           const float2 st = row_st[lane];
-          const int64_t lrow = lrow0 + i;
           if (!(st.y > 0.f) || !(st.y < 3.0e38f) || !(fabsf(st.x) < 3.0e38f)) lane_bad |= 8;
           if (i < g) {
             const int64_t qrow = off0 + i;
-            const int32_t x = a.tokens[qrow];
-            float p = 0.f, q = 0.f;
+            float p = 0.f;
             if (x < 0 || x >= a.V) {
               lane_bad |= 1;
             } else {
-              const float zx = load_logit(logits_row<BF16>(a, lrow), x, BF16);
               p = fast_exp2(fmaf(zx, c1, -st.x)) / st.y;
-              q = a.q_scalars ? a.q_scalars[qrow] : a.draft_probs[qrow * (int64_t)a.V + x];
               const Philox rnd = step_block(a.session_base + (uint32_t)b, (uint32_t)i, a.step_lo, a.step_hi, a.step_dev,
                                       a.seed_lo, a.seed_hi);
               const float r = u01(rnd.w[0]);

@@ -94,10 +94,8 @@ __global__ __launch_bounds__(256) void accept_scan_block(const BatchView a, Open
     const int64_t off0 = session_first_draft(a, b);
     const int32_t g = (int32_t)((a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma) - off0);
     const int32_t n = min(next_width, g + 1 - row_end);
-    if (threadIdx.x == 0) {
-      next_list[atomicAdd(next_count, 1)] = b;
-      sh_base = atomicAdd(next_n_rows, n);
-    }
+    if (threadIdx.x == 0) sh_base = atomicAdd(next_n_rows, n);
+    if (threadIdx.x == kWave) next_list[atomicAdd(next_count, 1)] = b;   // another wave: the two round trips overlap
     __syncthreads();
     const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
     for (int32_t k = threadIdx.x; k < n; k += blockDim.x) {
