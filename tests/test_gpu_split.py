@@ -259,3 +259,32 @@ def test_split_calls_reject_bad_arguments(ctx):
     assert D.dssd_residual_sample_from_p(ctx.handle, db, 0, check=False) == D.DSSD_ENOMEM
     assert D.load().dssd_residual_sample_from_p(None, None, None) == D.DSSD_EINVAL
     torch.cuda.synchronize()
+
+
+def test_edge_with_early_exit_exports_the_same_rows(ctx):
+    """The edge's calls with DSSD_FLAG_EARLY_EXIT (verify from q scalars, bonus draw, export of
+    P_n): records, bonus tokens and the exported rows are those of the default path, bit for bit."""
+    w = synth.Workload("split_ee", B=37, V=20000, gamma=0, dtype="bf16", gamma_range=(1, 12),
+                       sigmas=(0.3, 1.0), frac_q_equals_p=0.2)
+    inputs = synth.generate(w, seed=19, device=DEV)
+    t0, p0, qs, _, _ = run_edge(ctx, inputs, 5, 2, D.DSSD_F16)
+    assert D.dssd_set_early_exit_schedule(ctx.handle, (0, 2, 6)) == D.DSSD_OK
+    try:
+        batch = D.make_batch(inputs, seed=5, step=2, q_scalars=qs, flags=D.FLAG_EARLY_EXIT)
+        t1, out = D.alloc_out(inputs, DEV)
+        s = ctx.stream()
+        D.dssd_verify_batch(ctx.handle, batch, out, s)
+        D.dssd_bonus_sample(ctx.handle, batch, out, s)
+        p1 = torch.full_like(p0, -1.0)
+        D.dssd_export_p_rows(ctx.handle, batch, p1.data_ptr(), D.DSSD_F16, s)
+        torch.cuda.synchronize()
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
+    rej = t0["rejected"].cpu().numpy()
+    assert (rej == 1).any() and (rej == 0).any()
+    for k in ("accepted_len", "rejected", "status"):
+        assert torch.equal(t0[k], t1[k]), k
+    tok0, tok1 = t0["out_token"].cpu().numpy(), t1["out_token"].cpu().numpy()
+    assert (tok0[rej == 0] == tok1[rej == 0]).all()          # bonus tokens
+    assert torch.equal(p0, p1)                               # downlink payload
+    assert torch.isnan(t1["row_stats"]).any()                # rows really were skipped
