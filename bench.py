@@ -421,11 +421,11 @@ def main():
         el = time.perf_counter() - t0
         result["whole_step_call"] = {"entry": "dssd_step_fused", "ms_per_step": 1e3 * el / args.steps,
                                      "value": inputs["R_Q"] * args.steps / el, "unit": "positions/s"}
-    if not args.fused and not args.early_exit and not flags:
+    if not args.fused and not args.early_exit:
         # the same step when the caller allows rows after a session's first rejection to stay
         # unread (DSSD_FLAG_EARLY_EXIT): same records and tokens, fewer bytes.  A figure beside
         # the headline, which reads every row.
-        ee = D.make_batch(inputs, seed=args.seed, step=0, flags=D.FLAG_EARLY_EXIT)
+        ee = D.make_batch(inputs, seed=args.seed, step=0, flags=flags | D.FLAG_EARLY_EXIT)
         for k in range(args.warmup):
             ee.step = k
             ctx.step_fused(ee, out)

@@ -76,8 +76,8 @@ enum {
    * its bonus row.  accepted_len, rejected and out_token are bit-identical to the default path,
    * and so are row_stats, p_tok and q_tok for the rows and positions of the blocks that were
    * visited; entries of later blocks are NaN, and a fault (bad token, non-finite row) there
-   * goes unnoticed.  Honoured by dssd_verify_batch and dssd_step_fused; not combinable with
-   * DSSD_FLAG_SPARSE_SUPPORT (DSSD_EUNSUPPORTED). */
+   * goes unnoticed.  Honoured by dssd_verify_batch and dssd_step_fused; combines with
+   * DSSD_FLAG_SPARSE_SUPPORT. */
   DSSD_FLAG_EARLY_EXIT = 2
 };
 #define DSSD_MAX_SUPPORT 64

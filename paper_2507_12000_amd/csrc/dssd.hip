@@ -146,7 +146,6 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   if (b->B < 0 || b->V < 1 || b->gamma < 0 || b->total_drafts < 0) return DSSD_EINVAL;
   if (b->logits_dtype != DSSD_F32 && b->logits_dtype != DSSD_BF16) return DSSD_EINVAL;
   if (b->flags & ~(uint32_t)(DSSD_FLAG_SPARSE_SUPPORT | DSSD_FLAG_EARLY_EXIT)) return DSSD_EINVAL;
-  if ((b->flags & DSSD_FLAG_SPARSE_SUPPORT) && (b->flags & DSSD_FLAG_EARLY_EXIT)) return DSSD_EUNSUPPORTED;
   if (!b->draft_offsets && b->total_drafts != (int64_t)b->B * b->gamma) return DSSD_EINVAL;
   if (b->B > 0) {
     if (!b->logits) return DSSD_EINVAL;
@@ -235,6 +234,11 @@ static Schedule early_exit_schedule(const dssd_ctx* c, const dssd_batch* b, cons
 static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const BatchView& v, hipStream_t s,
                                        bool tail_bonus, const Schedule& sched) {
   const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
+  const bool sparse = (b->flags & DSSD_FLAG_SPARSE_SUPPORT) != 0;
+  if (sparse) {   // support lists start empty; the bonus draw comes from them, in dssd_bonus_sample
+    hipLaunchKernelGGL(zero_i32, dim3((unsigned)((v.R_L + 255) / 256)), dim3(256), 0, s, v.support_count, v.R_L);
+    tail_bonus = false;
+  }
   const int32_t* kEarlyExitBegin = sched.begin;
   const int kEarlyExitRounds = sched.n;
   const int32_t known_rows = b->draft_offsets ? 0x7FFFFFFF : b->gamma + 1;   // rows per session, if uniform
@@ -251,7 +255,9 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
         const int32_t w = std::min(end, known_rows);
         const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
         if (blocks > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
-#define DSSD_HEAD(BF, AL) DSSD_LAUNCH((row_chunk_stats_head<BF, AL>), blocks, s, v, w, c->open_count, 2 * kMaxRounds)
+#define DSSD_HEAD(BF, AL) do { \
+          if (sparse) DSSD_LAUNCH((row_chunk_stats_head<BF, AL, true>), blocks, s, v, w, c->open_count, 2 * kMaxRounds); \
+          else DSSD_LAUNCH((row_chunk_stats_head<BF, AL, false>), blocks, s, v, w, c->open_count, 2 * kMaxRounds); } while (0)
         if (bf16) { if (al) DSSD_HEAD(true, true); else DSSD_HEAD(true, false); }
         else      { if (al) DSSD_HEAD(false, true); else DSSD_HEAD(false, false); }
 #undef DSSD_HEAD
@@ -261,7 +267,9 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
         const int64_t worst = last ? rows_left : std::min<int64_t>(rows_left, (int64_t)b->B * (end - begin));
         const int64_t blocks = (std::min<int64_t>((worst * v.C + 3) / 4, 1 << 16) + 7) / 8 * 8;
         const RowTask* rows = c->open_rows[r & 1];
-#define DSSD_LIST(BF, AL) DSSD_LAUNCH((row_chunk_stats_list<BF, AL>), blocks, s, v, rows, n_rows + r)
+#define DSSD_LIST(BF, AL) do { \
+          if (sparse) DSSD_LAUNCH((row_chunk_stats_list<BF, AL, true>), blocks, s, v, rows, n_rows + r); \
+          else DSSD_LAUNCH((row_chunk_stats_list<BF, AL, false>), blocks, s, v, rows, n_rows + r); } while (0)
         if (bf16) { if (al) DSSD_LIST(true, true); else DSSD_LIST(true, false); }
         else      { if (al) DSSD_LIST(false, true); else DSSD_LIST(false, false); }
 #undef DSSD_LIST

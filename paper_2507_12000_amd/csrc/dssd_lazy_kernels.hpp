@@ -33,7 +33,7 @@ struct __attribute__((aligned(16))) RowTask {
 
 // Round 0: chunk statistics of rows [0, width) of every session, one wave per chunk.
 // zero[0..n_zero) is cleared by the first threads (the list counters of the rounds that follow).
-template <bool BF16, bool ALIGNED>
+template <bool BF16, bool ALIGNED, bool SUPPORT>
 __global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, int32_t width, int32_t* zero,
                                                             int32_t n_zero) {
   const int lane = threadIdx.x & 63;
@@ -50,13 +50,16 @@ __global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, i
   if (i > off1 - off0) return;                            // the session has fewer rows
   const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
   const int64_t lrow = off0 + b + i;
-  const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, lrow), c, a.V, c1, lane);
+  SupportRow sup{};
+  if constexpr (SUPPORT)
+    sup = SupportRow{a.support_count + lrow, a.support_idx + lrow * kMaxSupport, a.support_z + lrow * kMaxSupport};
+  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, lrow), c, a.V, c1, lane, sup);
   if (lane == 0) a.chunk_stats[lrow * a.C + c] = st;
 }
 
 // Later rounds: chunk statistics of the rows the accept launch before has listed, one wave per
 // chunk, grid-stride (the grid is fixed by the host, the list length is not known there).
-template <bool BF16, bool ALIGNED>
+template <bool BF16, bool ALIGNED, bool SUPPORT>
 __global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, const RowTask* rows,
                                                             const int32_t* n_rows) {
   const int lane = threadIdx.x & 63;
@@ -70,7 +73,11 @@ __global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, c
     const int64_t e = task / a.C;
     const int32_t c = (int32_t)(task - e * a.C);
     const RowTask t = rows[e];
-    const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, t.lrow), c, a.V, t.c1, lane);
+    SupportRow sup{};
+    if constexpr (SUPPORT)
+      sup = SupportRow{a.support_count + t.lrow, a.support_idx + t.lrow * kMaxSupport,
+                       a.support_z + t.lrow * kMaxSupport};
+    const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, t.lrow), c, a.V, t.c1, lane, sup);
     if (lane == 0) a.chunk_stats[t.lrow * a.C + c] = st;
   }
 }

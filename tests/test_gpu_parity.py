@@ -471,6 +471,35 @@ def test_sparse_support_mode(ctx, w):
     assert torch.equal(t2["out_token"], t["out_token"])
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["three_calls", "whole_step"])
+@pytest.mark.parametrize("w", SPARSE_CASES, ids=[w.name for w in SPARSE_CASES])
+def test_sparse_support_with_early_exit(ctx, w, fused):
+    """Both flags together (the paper's experiments sample with top-k = 10, and its loop stops at
+    the first rejection): the same records and tokens as sparse-support mode alone."""
+    inputs = synth.generate(w, seed=7, device=DEV)
+    seed, step = 17, 3
+    t0, out0 = D.alloc_out(inputs, DEV)
+    ctx.step(D.make_batch(inputs, seed=seed, step=step, flags=D.FLAG_SPARSE_SUPPORT), out0)
+    assert D.dssd_set_early_exit_schedule(ctx.handle, (0, 2, 5)) == D.DSSD_OK
+    try:
+        for rep in range(2):                                   # the second call reuses the lists
+            t1, out1 = D.alloc_out(inputs, DEV)
+            D.dssd_profile_reset(ctx.handle)
+            D.dssd_profile_enable(ctx.handle, True)
+            (ctx.step_fused if fused else ctx.step)(
+                D.make_batch(inputs, seed=seed, step=step, flags=D.FLAG_SPARSE_SUPPORT | D.FLAG_EARLY_EXIT), out1)
+            torch.cuda.synchronize()
+            D.dssd_profile_enable(ctx.handle, False)
+            assert D.dssd_profile_read(ctx.handle, D.K_ROW_STATS_BLOCK)[1] >= 1
+            assert D.dssd_profile_read(ctx.handle, D.K_RESID_MASS)[1] == 0
+            for k in ("accepted_len", "rejected", "out_token", "status"):
+                assert torch.equal(t0[k], t1[k]), (k, rep)
+            seen = ~torch.isnan(t1["p_tok"])
+            assert torch.equal(t0["p_tok"][seen], t1["p_tok"][seen])
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
+
+
 def test_sparse_support_overflow_is_reported(ctx):
     w = synth.Workload("dense_with_flag", B=5, V=3000, gamma=2, dtype="f32", sigmas=(1.0,))
     inputs = synth.generate(w, seed=1, device=DEV)
@@ -696,13 +725,11 @@ def test_early_exit_is_skipped_for_small_batches_by_default(ctx):
     assert D.dssd_set_early_exit_schedule(ctx.handle, (0,)) == D.DSSD_EINVAL
 
 
-def test_early_exit_refuses_sparse_support_and_reports_bad_sessions(ctx):
+def test_early_exit_reports_bad_sessions(ctx):
     w = synth.Workload("ee_bad", B=4, V=5000, gamma=3, dtype="f32", sigmas=(0.05,))
     inputs = synth.generate(w, seed=3, device=DEV)
     D.dssd_set_early_exit_schedule(ctx.handle, (0, 2))
     t, out = D.alloc_out(inputs, DEV)
-    both = D.make_batch(inputs, seed=1, step=0, flags=D.FLAG_EARLY_EXIT | D.FLAG_SPARSE_SUPPORT)
-    assert D.dssd_verify_batch(ctx.handle, both, out, ctx.stream(), check=False) == D.DSSD_EUNSUPPORTED
     bad = dict(inputs)
     bad["draft_tokens"] = inputs["draft_tokens"].clone()
     bad["draft_tokens"][3] = w.V + 5                       # session 1, position 0
