@@ -742,3 +742,38 @@ def test_early_exit_reports_bad_sessions(ctx):
         assert (int(t["accepted_len"][b]), int(t["rejected"][b]), int(t["out_token"][b])) == (0, 1, -1)
     assert int(t["out_token"][0]) >= 0
     D.dssd_set_early_exit_schedule(ctx.handle, ())
+
+
+BOUNDARY_V = {
+    # around one chunk, two chunks, and the 64-chunk batch of the row merge (bf16 chunk = 4096, fp32 = 2048)
+    "bf16": [4095, 4096, 4097, 8191, 8200, 64 * 4096 - 8, 64 * 4096],
+    "f32": [2047, 2048, 2049, 4100, 64 * 2048, 64 * 2048 + 4, 65 * 2048 + 1],
+}
+BOUNDARY_CASES = [synth.Workload(f"edge_{dt}_V{V}_g{g}", B=3, V=V, gamma=g, dtype=dt, sigmas=(0.3,),
+                                 frac_q_equals_p=0.34)
+                  for dt, Vs in BOUNDARY_V.items() for V in Vs for g in ((1, 3) if V > 100000 else (0, 2, 5))]
+BOUNDARY_CASES += [synth.Workload(f"edge_f32_V300_g{g}", B=3, V=300, gamma=g, dtype="f32", sigmas=(0.01,),
+                                  frac_q_equals_p=0.34) for g in (63, 64, 65, 130)]
+
+
+@pytest.mark.parametrize("w", BOUNDARY_CASES, ids=[w.name for w in BOUNDARY_CASES])
+def test_tile_boundaries(ctx, w):
+    """Shapes at the edges of the tiling: V one below / at / one above a chunk and the 64-chunk
+    merge batch, gamma at the 64-lane accept pass.  Oracle parity for the three calls; the
+    whole-step call and the early-exit rounds must give the same records and tokens."""
+    inputs, gpu, orc, rep = check(ctx, w, seed=5, step=2, workers=8, gen_seed=4)
+    batch = D.make_batch(inputs, seed=5, step=2)
+    t, out = D.alloc_out(inputs, DEV)
+    ctx.step_fused(batch, out)
+    torch.cuda.synchronize()
+    for k in gpu:
+        assert (gpu[k] == t[k].cpu().numpy()).all(), ("whole-step", k)
+    D.dssd_set_early_exit_schedule(ctx.handle, (0, 1, 3))
+    try:
+        t2, out2 = D.alloc_out(inputs, DEV)
+        ctx.step_fused(D.make_batch(inputs, seed=5, step=2, flags=D.FLAG_EARLY_EXIT), out2)
+        torch.cuda.synchronize()
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
+    for k in ("accepted_len", "rejected", "out_token", "status"):
+        assert (gpu[k] == t2[k].cpu().numpy()).all(), ("early-exit", k)
