@@ -34,7 +34,7 @@ struct dssd_ctx {
   RowTask* open_rows[2] = {nullptr, nullptr};   // and the rows such a round takes statistics of
   int32_t ee_begin[kMaxRounds] = {0};           // early-exit schedule set by the caller (ee_rounds > 0)
   int ee_rounds = 0;
-  int32_t* open_count = nullptr;                // [2 * kMaxRounds]: list lengths per round (sessions, then rows)
+  ListLengths* open_count = nullptr;            // [kMaxRounds]: lengths of the lists of round r
   int32_t* support_count = nullptr;
   int32_t* support_idx = nullptr;
   float* support_z = nullptr;
@@ -116,7 +116,7 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   c->open_list[1] = reinterpret_cast<int32_t*>(p);    p += align256(rows * sizeof(int32_t));
   c->open_rows[0] = reinterpret_cast<RowTask*>(p);    p += align256(rows * sizeof(RowTask));
   c->open_rows[1] = reinterpret_cast<RowTask*>(p);    p += align256(rows * sizeof(RowTask));
-  c->open_count = reinterpret_cast<int32_t*>(p);
+  c->open_count = reinterpret_cast<ListLengths*>(p);
   // arrival counters start at zero; every kernel that uses them leaves them at zero
   if (hipMemset(c->arrive_resid, 0, 2 * rows * sizeof(int32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
     (void)hipFree(c->workspace);
@@ -242,8 +242,6 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
   const int32_t* kEarlyExitBegin = sched.begin;
   const int kEarlyExitRounds = sched.n;
   const int32_t known_rows = b->draft_offsets ? 0x7FFFFFFF : b->gamma + 1;   // rows per session, if uniform
-  int32_t* n_sessions = c->open_count;              // [kMaxRounds] sessions listed for round r
-  int32_t* n_rows = c->open_count + kMaxRounds;     // [kMaxRounds] rows listed for round r
   for (int r = 0; r < kEarlyExitRounds; ++r) {
     const int32_t begin = kEarlyExitBegin[r];
     if (begin >= known_rows) break;
@@ -256,8 +254,8 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
         const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
         if (blocks > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
 #define DSSD_HEAD(BF, AL) do { \
-          if (sparse) DSSD_LAUNCH((row_chunk_stats_head<BF, AL, true>), blocks, s, v, w, c->open_count, 2 * kMaxRounds); \
-          else DSSD_LAUNCH((row_chunk_stats_head<BF, AL, false>), blocks, s, v, w, c->open_count, 2 * kMaxRounds); } while (0)
+          if (sparse) DSSD_LAUNCH((row_chunk_stats_head<BF, AL, true>), blocks, s, v, w, c->open_count, kMaxRounds); \
+          else DSSD_LAUNCH((row_chunk_stats_head<BF, AL, false>), blocks, s, v, w, c->open_count, kMaxRounds); } while (0)
         if (bf16) { if (al) DSSD_HEAD(true, true); else DSSD_HEAD(true, false); }
         else      { if (al) DSSD_HEAD(false, true); else DSSD_HEAD(false, false); }
 #undef DSSD_HEAD
@@ -268,8 +266,8 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
         const int64_t blocks = (std::min<int64_t>((worst * v.C + 3) / 4, 1 << 16) + 7) / 8 * 8;
         const RowTask* rows = c->open_rows[r & 1];
 #define DSSD_LIST(BF, AL) do { \
-          if (sparse) DSSD_LAUNCH((row_chunk_stats_list<BF, AL, true>), blocks, s, v, rows, n_rows + r); \
-          else DSSD_LAUNCH((row_chunk_stats_list<BF, AL, false>), blocks, s, v, rows, n_rows + r); } while (0)
+          if (sparse) DSSD_LAUNCH((row_chunk_stats_list<BF, AL, true>), blocks, s, v, rows, c->open_count + r); \
+          else DSSD_LAUNCH((row_chunk_stats_list<BF, AL, false>), blocks, s, v, rows, c->open_count + r); } while (0)
         if (bf16) { if (al) DSSD_LIST(true, true); else DSSD_LIST(true, false); }
         else      { if (al) DSSD_LIST(false, true); else DSSD_LIST(false, false); }
 #undef DSSD_LIST
@@ -277,16 +275,15 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
     }
     {
       Timed t(c, DSSD_K_ACCEPT, s);
-      const OpenSessions open{r ? c->open_list[r & 1] : nullptr, r ? n_sessions + r : nullptr};
+      const OpenSessions open{r ? c->open_list[r & 1] : nullptr, r ? c->open_count + r : nullptr};
       int32_t* next_list = last ? nullptr : c->open_list[(r + 1) & 1];
-      int32_t* next_count = last ? nullptr : n_sessions + r + 1;
       RowTask* next_rows = last ? nullptr : c->open_rows[(r + 1) & 1];
-      int32_t* next_n_rows = last ? nullptr : n_rows + r + 1;
+      ListLengths* next_lengths = last ? nullptr : c->open_count + r + 1;
       // the round after next starts at begin[r + 2]: the next one takes the rows in between, or all
       const int32_t next_width = last ? 0 : (r + 2 < kEarlyExitRounds ? kEarlyExitBegin[r + 2] - end : 0x7FFFFFFF);
 #define DSSD_ACC(BF, AL) do { \
-        if (tail_bonus) DSSD_LAUNCH((accept_scan_block<BF, AL, true>), b->B, s, v, open, begin, end, next_list, next_count, next_rows, next_n_rows, next_width); \
-        else DSSD_LAUNCH((accept_scan_block<BF, AL, false>), b->B, s, v, open, begin, end, next_list, next_count, next_rows, next_n_rows, next_width); } while (0)
+        if (tail_bonus) DSSD_LAUNCH((accept_scan_block<BF, AL, true>), b->B, s, v, open, begin, end, next_list, next_rows, next_lengths, next_width); \
+        else DSSD_LAUNCH((accept_scan_block<BF, AL, false>), b->B, s, v, open, begin, end, next_list, next_rows, next_lengths, next_width); } while (0)
       if (bf16) { if (al) DSSD_ACC(true, true); else DSSD_ACC(true, false); }
       else      { if (al) DSSD_ACC(false, true); else DSSD_ACC(false, false); }
 #undef DSSD_ACC

@@ -19,10 +19,16 @@ namespace dssd {
 
 constexpr int kMaxRounds = 8;
 
-// Sessions of a round: all of them (list == nullptr) or the `*count` entries of `list`.
+// Lengths of a round's two lists in one word, so that a session is appended to both with a
+// single atomic: sessions in the high half, rows in the low half.
+using ListLengths = unsigned long long;
+__device__ __forceinline__ int32_t listed_sessions(ListLengths n) { return (int32_t)(n >> 32); }
+__device__ __forceinline__ int32_t listed_rows(ListLengths n) { return (int32_t)(n & 0xFFFFFFFFull); }
+
+// Sessions of a round: all of them (list == nullptr) or the listed_sessions(*lengths) entries of `list`.
 struct OpenSessions {
   const int32_t* list;
-  const int32_t* count;
+  const ListLengths* lengths;
 };
 // One logits row to take statistics of, with its session's log2(e)/T.
 struct __attribute__((aligned(16))) RowTask {
@@ -32,9 +38,9 @@ struct __attribute__((aligned(16))) RowTask {
 };
 
 // Round 0: chunk statistics of rows [0, width) of every session, one wave per chunk.
-// zero[0..n_zero) is cleared by the first threads (the list counters of the rounds that follow).
+// zero[0..n_zero) is cleared by the first threads (the list lengths of the rounds that follow).
 template <bool BF16, bool ALIGNED, bool SUPPORT>
-__global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, int32_t width, int32_t* zero,
+__global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, int32_t width, ListLengths* zero,
                                                             int32_t n_zero) {
   const int lane = threadIdx.x & 63;
   if (blockIdx.x == 0 && threadIdx.x < n_zero) zero[threadIdx.x] = 0;
@@ -61,9 +67,9 @@ __global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, i
 // chunk, grid-stride (the grid is fixed by the host, the list length is not known there).
 template <bool BF16, bool ALIGNED, bool SUPPORT>
 __global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, const RowTask* rows,
-                                                            const int32_t* n_rows) {
+                                                            const ListLengths* lengths) {
   const int lane = threadIdx.x & 63;
-  const int64_t total = (int64_t)*n_rows * a.C;
+  const int64_t total = (int64_t)listed_rows(*lengths) * a.C;
   // each XCD walks one contiguous eighth of the list (the grid is a multiple of 8 workgroups)
   const int64_t nblk = (total + 3) / 4, per = (nblk + kXcds - 1) / kXcds;
   const int64_t first = (int64_t)(blockIdx.x % kXcds) * per;
@@ -84,15 +90,14 @@ __global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, c
 
 // Accept scan of rows [row_begin, row_end) for every open session, one workgroup per session.
 // A session that stays open is appended to next_list, and its next rows -- next_width of them,
-// or all that are left -- to next_rows.  TAIL_BONUS: a session whose drafts were all accepted
+// or all that are left -- to next_rows (one atomic on the packed lengths does both).  TAIL_BONUS: a session whose drafts were all accepted
 // also gets its bonus token here.
 template <bool BF16, bool ALIGNED, bool TAIL_BONUS>
 __global__ __launch_bounds__(256) void accept_scan_block(const BatchView a, OpenSessions open, int32_t row_begin,
-                                                         int32_t row_end, int32_t* next_list, int32_t* next_count,
-                                                         RowTask* next_rows, int32_t* next_n_rows,
-                                                         int32_t next_width) {
-  __shared__ int32_t sh_base;
-  if (open.list && (int32_t)blockIdx.x >= *open.count) return;
+                                                         int32_t row_end, int32_t* next_list, RowTask* next_rows,
+                                                         ListLengths* next_lengths, int32_t next_width) {
+  __shared__ ListLengths sh_at;
+  if (open.list && (int32_t)blockIdx.x >= listed_sessions(*open.lengths)) return;
   const int32_t b = open.list ? open.list[blockIdx.x] : (int32_t)blockIdx.x;
   Job job;
   const int32_t kind = accept_session<BF16>(a, b, &job, row_begin, row_end, true);
@@ -101,14 +106,15 @@ __global__ __launch_bounds__(256) void accept_scan_block(const BatchView a, Open
     const int64_t off0 = session_first_draft(a, b);
     const int32_t g = (int32_t)((a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma) - off0);
     const int32_t n = min(next_width, g + 1 - row_end);
-    if (threadIdx.x == 0) sh_base = atomicAdd(next_n_rows, n);
-    if (threadIdx.x == kWave) next_list[atomicAdd(next_count, 1)] = b;   // another wave: the two round trips overlap
+    if (threadIdx.x == 0) sh_at = atomicAdd(next_lengths, (1ull << 32) | (ListLengths)n);
     __syncthreads();
+    const ListLengths at = sh_at;
+    if (threadIdx.x == 0) next_list[listed_sessions(at)] = b;
     const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
     for (int32_t k = threadIdx.x; k < n; k += blockDim.x) {
       RowTask t;
       t.lrow = off0 + b + row_end + k; t.c1 = c1; t.pad = 0;
-      next_rows[sh_base + k] = t;
+      next_rows[listed_rows(at) + k] = t;
     }
     return;
   }
