@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
         "sources_sha256": "6eac15ab4213c4bb38360e712234c6b7b52efc319e3912c81d5cb5596ab3358d",
-        "bytes_per_launch": int((2426309.9 * 2.0 + 4776.8 * 1.0) * 1024),
+        "bytes_per_launch": int((2426304.9 * 2.0 + 4776.8 * 1.0) * 1024),
     },
 }
 
