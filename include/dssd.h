@@ -71,8 +71,8 @@ enum {
   /* Early exit: the caller allows the library to take the loop of Algorithm 2 ("while j <=
    * gamma and Flag = 1") at its word and read a session's logits rows only about as far as its
    * first rejected draft.  The rows are visited in rounds of growing blocks (by default [0,2),
-   * [2,6), the rest; fewer rounds for smaller batches, none where the extra launches would cost
-   * more than they save), and a session leaves as soon as a block holds its first rejection or
+   * [2,6), the rest; two blocks [0,3), the rest for smaller batches; none where the extra
+   * launches are expected to cost more than the unread rows save), and a session leaves as soon as a block holds its first rejection or
    * its bonus row.  accepted_len, rejected and out_token are bit-identical to the default path,
    * and so are row_stats, p_tok and q_tok for the rows and positions of the blocks that were
    * visited; entries of later blocks are NaN, and a fault (bad token, non-finite row) there

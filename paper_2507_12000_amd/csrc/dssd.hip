@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -215,20 +216,40 @@ static dssd_status launch_status() { return hipGetLastError() == hipSuccess ? DS
 // Early exit: rounds of (chunk statistics of a block of rows, accept scan of that block) over the
 // sessions that are still open.  `begin` holds the first row of every block; the last block is
 // open-ended.  Blocks grow because the share of open sessions shrinks geometrically while every
-// round costs two launches.  Measured on the benchmark workloads: three rounds {0,2,6} are best
-// from a few GB of logits on, two rounds {0,3} below that, and under about a quarter of a GB the
-// extra launches cost more than the rows they save (the default path runs instead).
+// round costs two launches.
 struct Schedule { int32_t begin[kMaxRounds]; int n; };
+
+// Which blocks, if any.  The host does not know how the drafts will fare, so it prices the
+// candidates with a fixed per-position acceptance of 0.8 (the middle of what speculative pairs
+// reach): rows a schedule leaves unread, times the row size, against about 20 us of extra
+// launches per round beyond the first, i.e. 140 MB of streaming.  Measured on the benchmark
+// workloads and a sweep of shapes: {0,2,6} wins from a few GB of logits on, {0,3} below that,
+// and small batches or short sessions are better off reading everything.
 static Schedule early_exit_schedule(const dssd_ctx* c, const dssd_batch* b, const BatchView& v) {
   if (c->ee_rounds > 0) {
     Schedule s{}; s.n = c->ee_rounds;
     for (int r = 0; r < s.n; ++r) s.begin[r] = c->ee_begin[r];
     return s;
   }
-  const double bytes = (double)v.R_L * b->V * (b->logits_dtype == DSSD_BF16 ? 2 : 4);
-  if (bytes < 256e6) return Schedule{{0}, 0};   // not worth it
-  if (bytes < 1.5e9) return Schedule{{0, 3}, 2};
-  return Schedule{{0, 2, 6}, 3};
+  static const Schedule candidates[2] = {{{0, 3}, 2}, {{0, 2, 6}, 3}};
+  const double rows = (double)v.R_L / std::max(b->B, 1);   // rows per session (mean, if ragged)
+  const double row_bytes = (double)b->V * (b->logits_dtype == DSSD_BF16 ? 2 : 4);
+  const double alpha = 0.8, round_cost_bytes = 140e6;
+  Schedule best{{0}, 0};
+  double best_gain = 0.0;
+  for (const Schedule& s : candidates) {
+    double read = 0.0, open = 1.0;   // open = share of sessions that reach the block
+    int rounds = 0;
+    for (int r = 0; r < s.n && s.begin[r] < rows; ++r) {
+      const double end = r + 1 < s.n ? std::min<double>(s.begin[r + 1], rows) : rows;
+      read += open * (end - s.begin[r]);
+      open = std::pow(alpha, end);
+      ++rounds;
+    }
+    const double gain = (rows - read) * b->B * row_bytes - (rounds - 1) * round_cost_bytes;
+    if (rounds > 1 && gain > best_gain) { best_gain = gain; best = s; }
+  }
+  return best;
 }
 
 static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const BatchView& v, hipStream_t s,
