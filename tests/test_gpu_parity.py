@@ -777,3 +777,46 @@ def test_tile_boundaries(ctx, w):
         D.dssd_set_early_exit_schedule(ctx.handle, ())
     for k in ("accepted_len", "rejected", "out_token", "status"):
         assert (gpu[k] == t2[k].cpu().numpy()).all(), ("early-exit", k)
+
+
+def _random_workload(k):
+    rng = np.random.default_rng(1000 + k)
+    dt = ("f32", "bf16")[int(rng.integers(2))]
+    V = int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(300, 9000)), int(rng.integers(9000, 70000))]))
+    ragged = bool(rng.integers(2))
+    gmax = int(rng.choice([1, 3, 8, 20]))
+    kw = dict(B=int(rng.integers(1, 40)), V=V, dtype=dt, zipf_s=float(rng.choice([0.0, 0.7, 1.2])),
+              sigmas=tuple(float(x) for x in rng.choice([0.05, 0.3, 1.0, 2.5], size=2)),
+              frac_q_equals_p=float(rng.choice([0.0, 0.2])), frac_q_uniform=float(rng.choice([0.0, 0.2])))
+    if ragged:
+        kw.update(gamma=0, gamma_range=(int(rng.integers(0, 2)), gmax))
+    else:
+        kw.update(gamma=int(rng.integers(0, gmax + 1)))
+    if rng.integers(3) == 0:
+        kw.update(temperature_range=(0.5, 1.6))
+    return synth.Workload(f"rand{k}_{dt}_V{V}", **kw)
+
+
+@pytest.mark.parametrize("k", range(40))
+def test_random_shapes(ctx, k):
+    """Seeded random shapes and session mixes: oracle parity for the three calls, and the same
+    records and tokens from the whole-step call and from early-exit rounds with a random schedule."""
+    w = _random_workload(k)
+    inputs, gpu, orc, rep = check(ctx, w, seed=900 + k, step=k, workers=8, gen_seed=k)
+    t, out = D.alloc_out(inputs, DEV)
+    ctx.step_fused(D.make_batch(inputs, seed=900 + k, step=k), out)
+    torch.cuda.synchronize()
+    for key in gpu:
+        assert (gpu[key] == t[key].cpu().numpy()).all(), ("whole-step", key)
+    rng = np.random.default_rng(k)
+    sched = (0,) + tuple(sorted(set(int(x) for x in rng.integers(1, 12, size=int(rng.integers(1, 5))))))
+    assert D.dssd_set_early_exit_schedule(ctx.handle, sched) == D.DSSD_OK
+    try:
+        t2, out2 = D.alloc_out(inputs, DEV)
+        (ctx.step if k % 2 else ctx.step_fused)(
+            D.make_batch(inputs, seed=900 + k, step=k, flags=D.FLAG_EARLY_EXIT), out2)
+        torch.cuda.synchronize()
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
+    for key in ("accepted_len", "rejected", "out_token", "status"):
+        assert (gpu[key] == t2[key].cpu().numpy()).all(), ("early-exit", sched, key)
