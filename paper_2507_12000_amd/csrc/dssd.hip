@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "dssd_fused_kernels.hpp"
@@ -213,6 +214,15 @@ struct Timed {
 
 static dssd_status launch_status() { return hipGetLastError() == hipSuccess ? DSSD_OK : DSSD_EHIP; }
 
+// Run-time booleans to template arguments: f receives one std::bool_constant per flag, in order.
+// FLAG(x) is the compile-time value of such an argument.
+template <class F> static void with_flags(F&& f) { f(); }
+template <class F, class... Rest> static void with_flags(F&& f, bool first, Rest... rest) {
+  if (first) with_flags([&](auto... r) { f(std::true_type{}, r...); }, rest...);
+  else       with_flags([&](auto... r) { f(std::false_type{}, r...); }, rest...);
+}
+#define FLAG(x) decltype(x)::value
+
 // Early exit: rounds of (chunk statistics of a block of rows, accept scan of that block) over the
 // sessions that are still open.  `begin` holds the first row of every block; the last block is
 // open-ended.  Blocks grow because the share of open sessions shrinks geometrically while every
@@ -274,24 +284,18 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
         const int32_t w = std::min(end, known_rows);
         const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
         if (blocks > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
-#define DSSD_HEAD(BF, AL) do { \
-          if (sparse) DSSD_LAUNCH((row_chunk_stats_head<BF, AL, true>), blocks, s, v, w, c->open_count, kMaxRounds); \
-          else DSSD_LAUNCH((row_chunk_stats_head<BF, AL, false>), blocks, s, v, w, c->open_count, kMaxRounds); } while (0)
-        if (bf16) { if (al) DSSD_HEAD(true, true); else DSSD_HEAD(true, false); }
-        else      { if (al) DSSD_HEAD(false, true); else DSSD_HEAD(false, false); }
-#undef DSSD_HEAD
+        with_flags([&](auto BF, auto AL, auto SP) {
+          DSSD_LAUNCH((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, s, v, w, c->open_count, kMaxRounds);
+        }, bf16, al, sparse);
       } else {
         // the rows listed by the accept launch before: at most every row that is left
         const int64_t rows_left = b->draft_offsets ? v.R_L : (int64_t)b->B * (known_rows - begin);
         const int64_t worst = last ? rows_left : std::min<int64_t>(rows_left, (int64_t)b->B * (end - begin));
         const int64_t blocks = (std::min<int64_t>((worst * v.C + 3) / 4, 1 << 16) + 7) / 8 * 8;
         const RowTask* rows = c->open_rows[r & 1];
-#define DSSD_LIST(BF, AL) do { \
-          if (sparse) DSSD_LAUNCH((row_chunk_stats_list<BF, AL, true>), blocks, s, v, rows, c->open_count + r); \
-          else DSSD_LAUNCH((row_chunk_stats_list<BF, AL, false>), blocks, s, v, rows, c->open_count + r); } while (0)
-        if (bf16) { if (al) DSSD_LIST(true, true); else DSSD_LIST(true, false); }
-        else      { if (al) DSSD_LIST(false, true); else DSSD_LIST(false, false); }
-#undef DSSD_LIST
+        with_flags([&](auto BF, auto AL, auto SP) {
+          DSSD_LAUNCH((row_chunk_stats_list<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, s, v, rows, c->open_count + r);
+        }, bf16, al, sparse);
       }
     }
     {
@@ -302,12 +306,10 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
       ListLengths* next_lengths = last ? nullptr : c->open_count + r + 1;
       // the round after next starts at begin[r + 2]: the next one takes the rows in between, or all
       const int32_t next_width = last ? 0 : (r + 2 < kEarlyExitRounds ? kEarlyExitBegin[r + 2] - end : 0x7FFFFFFF);
-#define DSSD_ACC(BF, AL) do { \
-        if (tail_bonus) DSSD_LAUNCH((accept_scan_block<BF, AL, true>), b->B, s, v, open, begin, end, next_list, next_rows, next_lengths, next_width); \
-        else DSSD_LAUNCH((accept_scan_block<BF, AL, false>), b->B, s, v, open, begin, end, next_list, next_rows, next_lengths, next_width); } while (0)
-      if (bf16) { if (al) DSSD_ACC(true, true); else DSSD_ACC(true, false); }
-      else      { if (al) DSSD_ACC(false, true); else DSSD_ACC(false, false); }
-#undef DSSD_ACC
+      with_flags([&](auto BF, auto AL, auto TB) {
+        DSSD_LAUNCH((accept_scan_block<FLAG(BF), FLAG(AL), FLAG(TB)>), b->B, s, v, open, begin, end, next_list,
+                    next_rows, next_lengths, next_width);
+      }, bf16, al, tail_bonus);
     }
     if (last) break;
   }
@@ -331,21 +333,17 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
     hipLaunchKernelGGL(zero_i32, dim3((unsigned)((v.R_L + 255) / 256)), dim3(256), 0, s, v.support_count, v.R_L);
   {
     Timed t(c, DSSD_K_ROW_STATS, s);
-#define DSSD_STATS(BF, AL) do { if (sparse) DSSD_LAUNCH((row_chunk_stats<BF, AL, true>), grid, s, v); \
-                                else DSSD_LAUNCH((row_chunk_stats<BF, AL, false>), grid, s, v); } while (0)
-    if (bf16) { if (al) DSSD_STATS(true, true); else DSSD_STATS(true, false); }
-    else      { if (al) DSSD_STATS(false, true); else DSSD_STATS(false, false); }
-#undef DSSD_STATS
+    with_flags([&](auto BF, auto AL, auto SP) {
+      DSSD_LAUNCH((row_chunk_stats<FLAG(BF), FLAG(AL), FLAG(SP)>), grid, s, v);
+    }, bf16, al, sparse);
   }
   {
     Timed t(c, DSSD_K_ACCEPT, s);
     const unsigned g2 = (unsigned)b->B;   // one workgroup per session
-    if (tail_bonus && !sparse) {
-      if (bf16) { if (al) DSSD_LAUNCH((accept_scan_bonus<true, true>), g2, s, v); else DSSD_LAUNCH((accept_scan_bonus<true, false>), g2, s, v); }
-      else      { if (al) DSSD_LAUNCH((accept_scan_bonus<false, true>), g2, s, v); else DSSD_LAUNCH((accept_scan_bonus<false, false>), g2, s, v); }
-    } else {
-      if (bf16) DSSD_LAUNCH((accept_scan<true>), g2, s, v); else DSSD_LAUNCH((accept_scan<false>), g2, s, v);
-    }
+    if (tail_bonus && !sparse)
+      with_flags([&](auto BF, auto AL) { DSSD_LAUNCH((accept_scan_bonus<FLAG(BF), FLAG(AL)>), g2, s, v); }, bf16, al);
+    else
+      with_flags([&](auto BF) { DSSD_LAUNCH((accept_scan<FLAG(BF)>), g2, s, v); }, bf16);
   }
   return launch_status();
 }
@@ -368,7 +366,7 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   if (b->flags & DSSD_FLAG_SPARSE_SUPPORT) {   // draw from the recorded support: no pass over V
     Timed t(c, DSSD_K_RESID_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
-    if (bf16) DSSD_LAUNCH((pick_sparse<true, true>), g2, s, v); else DSSD_LAUNCH((pick_sparse<false, true>), g2, s, v);
+    with_flags([&](auto BF) { DSSD_LAUNCH((pick_sparse<FLAG(BF), true>), g2, s, v); }, bf16);
     return launch_status();
   }
   const int32_t groups = (v.C + 3) / 4;
@@ -378,17 +376,14 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   const bool fuse = (int64_t)b->B * v.C <= 4096;
   {
     Timed t(c, DSSD_K_RESID_MASS, s);
-#define DSSD_RESID(BF, AL) do { if (fuse) DSSD_LAUNCH((resid_mass<BF, AL, true>), grid, s, v, groups); \
-                                else DSSD_LAUNCH((resid_mass<BF, AL, false>), grid, s, v, groups); } while (0)
-    if (bf16) { if (al) DSSD_RESID(true, true); else DSSD_RESID(true, false); }
-    else      { if (al) DSSD_RESID(false, true); else DSSD_RESID(false, false); }
-#undef DSSD_RESID
+    with_flags([&](auto BF, auto AL, auto FP) {
+      DSSD_LAUNCH((resid_mass<FLAG(BF), FLAG(AL), FLAG(FP)>), grid, s, v, groups);
+    }, bf16, al, fuse);
   }
   if (!fuse) {
     Timed t(c, DSSD_K_RESID_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
-    if (bf16) { if (al) DSSD_LAUNCH((pick_token<true, true, true>), g2, s, v); else DSSD_LAUNCH((pick_token<true, false, true>), g2, s, v); }
-    else      { if (al) DSSD_LAUNCH((pick_token<false, true, true>), g2, s, v); else DSSD_LAUNCH((pick_token<false, false, true>), g2, s, v); }
+    with_flags([&](auto BF, auto AL) { DSSD_LAUNCH((pick_token<FLAG(BF), FLAG(AL), true>), g2, s, v); }, bf16, al);
   }
   return launch_status();
 }
@@ -402,14 +397,13 @@ extern "C" dssd_status dssd_bonus_sample(dssd_ctx* c, const dssd_batch* b, dssd_
   if (b->flags & DSSD_FLAG_SPARSE_SUPPORT) {
     Timed t(c, DSSD_K_BONUS_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
-    if (bf16) DSSD_LAUNCH((pick_sparse<true, false>), g2, s, v); else DSSD_LAUNCH((pick_sparse<false, false>), g2, s, v);
+    with_flags([&](auto BF) { DSSD_LAUNCH((pick_sparse<FLAG(BF), false>), g2, s, v); }, bf16);
     return launch_status();
   }
   {
     Timed t(c, DSSD_K_BONUS_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
-    if (bf16) { if (al) DSSD_LAUNCH((pick_token<true, true, false>), g2, s, v); else DSSD_LAUNCH((pick_token<true, false, false>), g2, s, v); }
-    else      { if (al) DSSD_LAUNCH((pick_token<false, true, false>), g2, s, v); else DSSD_LAUNCH((pick_token<false, false, false>), g2, s, v); }
+    with_flags([&](auto BF, auto AL) { DSSD_LAUNCH((pick_token<FLAG(BF), FLAG(AL), false>), g2, s, v); }, bf16, al);
   }
   return launch_status();
 }
@@ -448,11 +442,9 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
     Timed t(c, DSSD_K_FUSED_STEP, s);
     const unsigned grid = (unsigned)(groups * b->B);
     const int32_t g32 = (int32_t)groups;
-#define DSSD_FUSED(BF, AL) do { if (single) DSSD_LAUNCH((fused_small_step<BF, AL, true>), grid, s, v, g32, c->arrive_stats); \
-                                else DSSD_LAUNCH((fused_small_step<BF, AL, false>), grid, s, v, g32, c->arrive_stats); } while (0)
-    if (bf16) { if (al) DSSD_FUSED(true, true); else DSSD_FUSED(true, false); }
-    else      { if (al) DSSD_FUSED(false, true); else DSSD_FUSED(false, false); }
-#undef DSSD_FUSED
+    with_flags([&](auto BF, auto AL, auto TR) {
+      DSSD_LAUNCH((fused_small_step<FLAG(BF), FLAG(AL), FLAG(TR)>), grid, s, v, g32, c->arrive_stats);
+    }, bf16, al, single);
   }
   if (pair && b->total_drafts > 0) {
     const dssd_status r = launch_status();
@@ -500,12 +492,9 @@ extern "C" dssd_status dssd_export_p_rows(dssd_ctx* c, const dssd_batch* b, void
   const unsigned grid = (unsigned)(groups * b->B);
   {
     Timed t(c, DSSD_K_EXPORT_P, s);
-#define DSSD_EXPORT(BF, AL, H) DSSD_LAUNCH((export_p_rows<BF, AL, H>), grid, s, v, groups, p_rows)
-    if (bf16) { if (al) { if (f16) DSSD_EXPORT(true, true, true); else DSSD_EXPORT(true, true, false); }
-                else    { if (f16) DSSD_EXPORT(true, false, true); else DSSD_EXPORT(true, false, false); } }
-    else      { if (al) { if (f16) DSSD_EXPORT(false, true, true); else DSSD_EXPORT(false, true, false); }
-                else    { if (f16) DSSD_EXPORT(false, false, true); else DSSD_EXPORT(false, false, false); } }
-#undef DSSD_EXPORT
+    with_flags([&](auto BF, auto AL, auto H) {
+      DSSD_LAUNCH((export_p_rows<FLAG(BF), FLAG(AL), FLAG(H)>), grid, s, v, groups, p_rows);
+    }, bf16, al, f16);
   }
   return launch_status();
 }
@@ -540,14 +529,12 @@ extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_devic
   {
     Timed t(c, DSSD_K_DEVICE_MASS, s);
     const unsigned grid = (unsigned)(groups * b->B);
-    if (f16) { if (al) DSSD_LAUNCH((device_resid_mass<true, true>), grid, s, d, groups); else DSSD_LAUNCH((device_resid_mass<true, false>), grid, s, d, groups); }
-    else     { if (al) DSSD_LAUNCH((device_resid_mass<false, true>), grid, s, d, groups); else DSSD_LAUNCH((device_resid_mass<false, false>), grid, s, d, groups); }
+    with_flags([&](auto H, auto AL) { DSSD_LAUNCH((device_resid_mass<FLAG(H), FLAG(AL)>), grid, s, d, groups); }, f16, al);
   }
   {
     Timed t(c, DSSD_K_DEVICE_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
-    if (f16) { if (al) DSSD_LAUNCH((device_pick<true, true>), g2, s, d); else DSSD_LAUNCH((device_pick<true, false>), g2, s, d); }
-    else     { if (al) DSSD_LAUNCH((device_pick<false, true>), g2, s, d); else DSSD_LAUNCH((device_pick<false, false>), g2, s, d); }
+    with_flags([&](auto H, auto AL) { DSSD_LAUNCH((device_pick<FLAG(H), FLAG(AL)>), g2, s, d); }, f16, al);
   }
   return launch_status();
 }
