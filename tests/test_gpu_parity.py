@@ -820,3 +820,21 @@ def test_random_shapes(ctx, k):
         D.dssd_set_early_exit_schedule(ctx.handle, ())
     for key in ("accepted_len", "rejected", "out_token", "status"):
         assert (gpu[key] == t2[key].cpu().numpy()).all(), ("early-exit", sched, key)
+
+
+def test_many_sessions():
+    """A batch of 60 000 short sessions (grids of one workgroup per session, list lengths far
+    above one workgroup's worth): oracle parity, and the early-exit rounds give the same records."""
+    w = synth.Workload("many_sessions", B=60000, V=128, gamma=0, dtype="f32", gamma_range=(0, 4),
+                       sigmas=(0.5, 1.5), frac_q_equals_p=0.1, frac_q_uniform=0.1)
+    big = D.Context(DEV, max_rows=w.B * 5, max_V=w.V)
+    try:
+        inputs, gpu, orc, rep = check(big, w, seed=11, step=1, workers=1, gen_seed=6)
+        D.dssd_set_early_exit_schedule(big.handle, (0, 1, 3))
+        t, out = D.alloc_out(inputs, DEV)
+        big.step_fused(D.make_batch(inputs, seed=11, step=1, flags=D.FLAG_EARLY_EXIT), out)
+        torch.cuda.synchronize()
+        for key in ("accepted_len", "rejected", "out_token", "status"):
+            assert (gpu[key] == t[key].cpu().numpy()).all(), key
+    finally:
+        big.close()
