@@ -439,6 +439,38 @@ def main():
         result["early_exit_mode"] = {"entry": "dssd_step_fused + DSSD_FLAG_EARLY_EXIT",
                                      "ms_per_step": 1e3 * el / args.steps,
                                      "value": inputs["R_Q"] * args.steps / el, "unit": "positions/s"}
+    if not args.fused and not args.early_exit:
+        # two independent batches in flight, one context and one stream each (here: the same
+        # inputs, separate outputs and workspaces): the launches of one fill the ramps and tails
+        # of the other.  Throughput of a server with more than one batch queued; not the headline.
+        ctx2 = D.Context(dev, max_rows=inputs["R_L"], max_V=w.V)
+        outs2, out2 = D.alloc_out(inputs, dev, debug=False)
+        pairs = [(ctx, batch, out, torch.cuda.Stream()), (ctx2, D.make_batch(inputs, seed=args.seed, step=0, flags=flags),
+                                                          out2, torch.cuda.Stream())]
+        for _, _, _, st in pairs:
+            st.wait_stream(torch.cuda.current_stream())
+
+        def both(n, first_step):
+            for k in range(n):
+                cx, bt, ot, st = pairs[k % 2]
+                with torch.cuda.stream(st):
+                    bt.step = first_step + k
+                    cx.step_fused(bt, ot)
+        result["two_batches_in_flight"] = {"entry": "dssd_step_fused, two contexts on two streams"}
+        for name, fl in (("default", flags), ("early_exit", flags | D.FLAG_EARLY_EXIT)):
+            for _, bt, _, _ in pairs:
+                bt.flags = fl
+            both(args.warmup, 0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            both(args.steps, args.warmup)
+            torch.cuda.synchronize()
+            el = time.perf_counter() - t0
+            result["two_batches_in_flight"][name] = {"ms_per_step": 1e3 * el / args.steps,
+                                                      "value": inputs["R_Q"] * args.steps / el,
+                                                      "unit": "positions/s"}
+        batch.flags = flags
+        ctx2.close()
     if args.split:
         result["split_path"] = time_split_path(ctx, D, torch, inputs, outs, args)
     if not args.no_cpu_baseline:
