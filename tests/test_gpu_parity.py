@@ -838,3 +838,32 @@ def test_many_sessions():
             assert (gpu[key] == t[key].cpu().numpy()).all(), key
     finally:
         big.close()
+
+
+def test_two_contexts_on_two_streams_do_not_disturb_each_other(ctx):
+    """Two batches in flight, one context and one stream each (the workspaces are per context):
+    every step gives what the same call gives alone."""
+    w = synth.Workload("two_streams", B=300, V=30000, gamma=0, dtype="bf16", gamma_range=(1, 9),
+                       sigmas=(0.3, 1.2), frac_q_equals_p=0.1)
+    inputs = synth.generate(w, seed=31, device=DEV)
+    other = D.Context(DEV, max_rows=inputs["R_L"], max_V=w.V)
+    try:
+        D.dssd_set_early_exit_schedule(other.handle, (0, 2, 5))
+        alone = [gpu_step(ctx, inputs, 50 + k, k) for k in range(6)]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for st in streams:
+            st.wait_stream(torch.cuda.current_stream())
+        held = []
+        for k in range(6):
+            cx = (ctx, other)[k % 2]
+            t, out = D.alloc_out(inputs, DEV)
+            with torch.cuda.stream(streams[k % 2]):
+                cx.step_fused(D.make_batch(inputs, seed=50 + k, step=k,
+                                           flags=D.FLAG_EARLY_EXIT if k % 2 else 0), out)
+            held.append(t)
+        torch.cuda.synchronize()
+        for k in range(6):
+            for key in ("accepted_len", "rejected", "out_token", "status"):
+                assert (alone[k][key] == held[k][key].cpu().numpy()).all(), (k, key)
+    finally:
+        other.close()
