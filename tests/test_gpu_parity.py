@@ -867,3 +867,37 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other(ctx):
                 assert (alone[k][key] == held[k][key].cpu().numpy()).all(), (k, key)
     finally:
         other.close()
+
+
+def test_early_exit_never_touches_rows_after_the_stopping_block(ctx):
+    """Rows after the block that holds a session's first rejection are poisoned with NaN: the
+    early-exit rounds still give the clean batch's records and tokens (those rows are never
+    used), while the default path, which reads every row, reports the sessions as bad."""
+    w = synth.Workload("ee_poison", B=50, V=6000, gamma=0, dtype="bf16", gamma_range=(4, 14), sigmas=(0.5, 1.5))
+    inputs = synth.generate(w, seed=41, device=DEV)
+    clean = gpu_step(ctx, inputs, 8, 2)
+    off = inputs["draft_offsets"].cpu().numpy().astype(np.int64)
+    sched = (0, 2, 5)
+    logits = inputs["logits"].clone()
+    hit = []
+    for b in range(w.B):
+        n, g = int(clean["accepted_len"][b]), int(off[b + 1] - off[b])
+        later = [s0 for s0 in sched if s0 > n]
+        stop = later[0] if later else g + 1
+        if stop <= g:
+            l0 = int(off[b]) + b
+            logits[l0 + stop:l0 + g + 1] = float("nan")
+            hit.append(b)
+    assert len(hit) > 10
+    poisoned = dict(inputs, logits=logits)
+    D.dssd_set_early_exit_schedule(ctx.handle, sched)
+    try:
+        t, out = D.alloc_out(poisoned, DEV)
+        ctx.step_fused(D.make_batch(poisoned, seed=8, step=2, flags=D.FLAG_EARLY_EXIT), out)
+        torch.cuda.synchronize()
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
+    for key in ("accepted_len", "rejected", "out_token", "status"):
+        assert (clean[key] == t[key].cpu().numpy()).all(), key
+    full = gpu_step(ctx, poisoned, 8, 2)
+    assert all(full["status"][b] & D.SESSION_BAD_ROW for b in hit)

@@ -373,3 +373,32 @@ def test_top_k_truncated_supports():
             assert out["p_tok"][b * g + n] < Q[b * g + n, tok[b * g + n]] or out["p_tok"][b * g + n] == 0.0
             P = O.softmax_row(stored[lrow], O.BF16)[0]
             assert P[res["token"][b]] > Q[b * g + n, res["token"][b]]
+
+
+def test_rows_after_the_first_rejection_do_not_matter():
+    """Algorithm 2 stops at the first rejected draft: whatever the target and draft rows hold
+    after it cannot change (n, rejected, token).  Poison them and compare.  (This is what makes
+    reading a session's rows only as far as its first rejection legitimate.)"""
+    from paper_2507_12000_amd import synth
+    import parity
+    w = synth.Workload("poison", B=40, V=700, gamma=0, dtype="f32", gamma_range=(1, 9), sigmas=(0.5, 1.5),
+                       frac_q_equals_p=0.1)
+    inputs = synth.generate(w, seed=5, device="cpu")
+    h = parity.to_numpy_inputs(inputs)
+    ref = parity.run_oracle(h, 21, 3, workers=2)
+    off = ref["offsets"]
+    logits = h["logits"].copy()
+    q = h["draft_probs"].copy()
+    poisoned = 0
+    for b in range(w.B):
+        n, g = int(ref["res"][b]["n"]), int(off[b + 1] - off[b])
+        if n < g:                                    # rejected at n: rows n+1..g, draft rows n+1..g-1
+            l0 = int(off[b]) + b
+            logits[l0 + n + 1:l0 + g + 1] = 1.0e30
+            q[int(off[b]) + n + 1:int(off[b]) + g] = 0.123
+            poisoned += g - n
+    assert poisoned > 20
+    h2 = dict(h, logits=logits, draft_probs=q)
+    got = parity.run_oracle(h2, 21, 3, workers=2)
+    for k in ("n", "rejected", "token"):
+        assert (got["res"][k] == ref["res"][k]).all(), k
