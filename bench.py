@@ -153,6 +153,53 @@ def time_graph_replays(ctx, D, torch, run, batch, out, inputs, w, args):
             "roofline": None, "cpu_baseline": None}
 
 
+def time_topk_lists(ctx, D, torch, inputs, outs, out, args):
+    """The same truncated batch handed over as top-k lists (dssd_step_topk): k (id, value) pairs
+    per row instead of V values, so nothing of size V is streamed.  What the step costs when the
+    sampler upstream already holds the lists.  Beside the headline, never `value`."""
+    def pack(x, used, k):
+        chunks_i, chunks_v = [], []
+        for r0 in range(0, x.shape[0], 512):                 # by slabs: a temporary of the row size each
+            xs, us = x[r0:r0 + 512].float(), used[r0:r0 + 512]
+            vals, idx = torch.topk(torch.where(us, xs, torch.full_like(xs, -float("inf"))), k, dim=1)
+            keep = torch.isfinite(vals)
+            chunks_i.append(torch.where(keep, idx, torch.full_like(idx, -1)).to(torch.int32))
+            chunks_v.append(torch.where(keep, vals, torch.zeros_like(vals)))
+        return torch.cat(chunks_i).contiguous(), torch.cat(chunks_v).contiguous()
+
+    lg, q = inputs["logits"], inputs["draft_probs"]
+    k, cut = 1, 0
+    for x, used in ((lg, torch.isfinite), (q, lambda t: t > 0)):
+        for r0 in range(0, x.shape[0], 512):
+            n = used(x[r0:r0 + 512]).sum(1)
+            cut += int((n > 64).sum().item())
+            k = max(k, int(n.clamp(max=64).max().item()))
+    # rows with more than 64 entries (the sessions whose draft is uniform over V) keep their 64
+    # largest: a timing stand-in, counted below
+    p_idx, p_logit = pack(lg, torch.isfinite(lg), k)
+    q_idx, q_prob = pack(q, q > 0, k)
+    off, it = inputs.get("draft_offsets"), inputs.get("inv_temperature")
+    dp = lambda t: None if t is None else t.data_ptr()       # noqa: E731
+    tb = D.dssd_topk_batch(B=inputs["B"], k=k, gamma=inputs["gamma"], V=inputs["V"], total_drafts=inputs["R_Q"],
+                           draft_offsets=dp(off), p_idx=dp(p_idx), p_logit=dp(p_logit), q_idx=dp(q_idx),
+                           q_prob=dp(q_prob), draft_tokens=dp(inputs["draft_tokens"]), inv_temperature=dp(it),
+                           seed=args.seed, step=0, session_base=0, reserved=0, step_counter=None)
+    s = ctx.stream()
+    for n in range(args.warmup):
+        tb.step = n
+        D.dssd_step_topk(ctx.handle, tb, out, s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for n in range(args.steps):
+        tb.step = args.warmup + n
+        D.dssd_step_topk(ctx.handle, tb, out, s)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    return {"entry": "dssd_step_topk", "k": k, "ms_per_step": 1e3 * el / args.steps,
+            "value": inputs["R_Q"] * args.steps / el, "unit": "positions/s",
+            "list_bytes_per_step": int((inputs["R_L"] + inputs["R_Q"]) * k * 8), "rows_cut_to_64_entries": cut}
+
+
 def time_split_path(ctx, D, torch, inputs, outs, args):
     """The same batch through the paper's split: the edge verifies from the uploaded scalars
     q_i(x_i) and draws bonus tokens, exports P_n of every rejected session as fp16 (the downlink
@@ -474,6 +521,8 @@ def main():
                                                       "unit": "positions/s"}
         batch.flags = flags
         ctx2.close()
+    if args.top_k > 0 and not args.headline_only:
+        result["topk_lists"] = time_topk_lists(ctx, D, torch, inputs, outs, out, args)
     if args.split:
         result["split_path"] = time_split_path(ctx, D, torch, inputs, outs, args)
     if not args.no_cpu_baseline:

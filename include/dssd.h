@@ -231,7 +231,8 @@ const char *dssd_status_str(dssd_status s);
  * the device-side redraw, 8 the single-launch step of dssd_step_fused, 9 the read probe. */
 enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
        DSSD_K_BONUS_PICK = 4, DSSD_K_EXPORT_P = 5, DSSD_K_DEVICE_MASS = 6, DSSD_K_DEVICE_PICK = 7,
-       DSSD_K_FUSED_STEP = 8, DSSD_K_READ_PROBE = 9, DSSD_K_ROW_STATS_BLOCK = 10, DSSD_K_COUNT = 11 };
+       DSSD_K_FUSED_STEP = 8, DSSD_K_READ_PROBE = 9, DSSD_K_ROW_STATS_BLOCK = 10, DSSD_K_TOPK_STEP = 11,
+       DSSD_K_COUNT = 12 };
 dssd_status dssd_profile_enable(dssd_ctx *ctx, uint32_t kernel_mask);
 /* Synchronises the recorded events, returns the summed duration (ms) and number of launches
  * of one kernel since the last reset. */
@@ -243,6 +244,33 @@ const char *dssd_kernel_name(int kernel_id);
  * aligned) with the access pattern of the row-statistics kernel and no arithmetic.  Its rate is
  * the read ceiling that kernel can be held against on the chip at hand. */
 dssd_status dssd_probe_read(dssd_ctx *ctx, const void *buf, size_t bytes, void *hip_stream);
+
+/* The step on top-k lists (the paper's experiments sample with top-k = 10, Sec. 4): both models'
+ * rows arrive as k (token id, value) pairs instead of V values.  It computes what the dense step
+ * computes on rows that are -inf (target logits) / 0 (draft probabilities) outside the lists:
+ * P_i = softmax of the k listed logits times 1/T, accept iff r*q < p with p, q = 0 for a token
+ * outside the respective list, redraw from norm(max(0, P_n - Q_n)) (its support lies inside the
+ * target's list) or bonus token from P_gamma, both by inverse CDF in vocabulary order, the same
+ * Philox blocks.  One launch; rows after a session's first rejection are not read, and their
+ * row_stats / p_tok / q_tok entries are NaN.  Ids within one list must be distinct; -1 marks an
+ * unused entry; the lists need not be sorted.  Layout of sessions, rows and outputs as in
+ * dssd_batch / dssd_out.  All pointers are device pointers, 4-byte aligned. */
+typedef struct {
+  int32_t B, k, gamma, V;       /* k in [1, 64] entries per list; V > 0 range-checks the draft
+                                   tokens, V = 0 does not                                          */
+  int64_t total_drafts;         /* R_Q                                                             */
+  const int32_t *draft_offsets; /* [B+1] or NULL                                                   */
+  const int32_t *p_idx;         /* [R_L, k] token ids of the target's list                         */
+  const float *p_logit;         /* [R_L, k] their logits                                           */
+  const int32_t *q_idx;         /* [R_Q, k] token ids of the draft's list                          */
+  const float *q_prob;          /* [R_Q, k] their probabilities, as the draft sampled from them    */
+  const int32_t *draft_tokens;  /* [R_Q]                                                           */
+  const float *inv_temperature; /* [B] or NULL                                                     */
+  uint64_t seed, step;
+  uint32_t session_base, reserved;
+  const uint64_t *step_counter; /* device or NULL: as in dssd_batch                                */
+} dssd_topk_batch;
+dssd_status dssd_step_topk(dssd_ctx *ctx, const dssd_topk_batch *batch, dssd_out *out, void *hip_stream);
 
 /* Checking aid: the Philox4x32-10 blocks the step draws from, for the rectangle of sessions
  * [session_first, +n_sessions) x positions [position_first, +n_positions) (32-bit wrap-around),

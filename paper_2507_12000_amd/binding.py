@@ -17,12 +17,12 @@ FLAG_SPARSE_SUPPORT = 1
 FLAG_EARLY_EXIT = 2
 MAX_SUPPORT = 64
 K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
-K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_ROW_STATS_BLOCK, K_COUNT = 5, 6, 7, 8, 9, 10, 11
+K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_ROW_STATS_BLOCK, K_TOPK_STEP, K_COUNT = 5, 6, 7, 8, 9, 10, 11, 12
 
 # every symbol include/dssd.h declares
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
-           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_status_str", "dssd_profile_enable",
+           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_step_topk", "dssd_status_str", "dssd_profile_enable",
            "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name", "dssd_probe_read")
 
 
@@ -41,6 +41,15 @@ class dssd_device_batch(C.Structure):
                 ("p_rows", C.c_void_p), ("accepted_len", C.c_void_p), ("rejected", C.c_void_p),
                 ("seed", C.c_uint64), ("step", C.c_uint64), ("session_base", C.c_uint32),
                 ("reserved", C.c_uint32), ("out_token", C.c_void_p), ("status", C.c_void_p),
+                ("step_counter", C.c_void_p)]
+
+
+class dssd_topk_batch(C.Structure):
+    _fields_ = [("B", C.c_int32), ("k", C.c_int32), ("gamma", C.c_int32), ("V", C.c_int32),
+                ("total_drafts", C.c_int64), ("draft_offsets", C.c_void_p), ("p_idx", C.c_void_p),
+                ("p_logit", C.c_void_p), ("q_idx", C.c_void_p), ("q_prob", C.c_void_p),
+                ("draft_tokens", C.c_void_p), ("inv_temperature", C.c_void_p), ("seed", C.c_uint64),
+                ("step", C.c_uint64), ("session_base", C.c_uint32), ("reserved", C.c_uint32),
                 ("step_counter", C.c_void_p)]
 
 
@@ -92,6 +101,8 @@ def load():
         f = getattr(L, name)
         f.argtypes = [P, C.POINTER(dssd_batch), C.POINTER(dssd_out), P]
         f.restype = C.c_int
+    L.dssd_step_topk.argtypes = [P, C.POINTER(dssd_topk_batch), C.POINTER(dssd_out), P]
+    L.dssd_step_topk.restype = C.c_int
     L.dssd_export_p_rows.argtypes = [P, C.POINTER(dssd_batch), P, C.c_int32, P]
     L.dssd_export_p_rows.restype = C.c_int
     L.dssd_residual_sample_from_p.argtypes = [P, C.POINTER(dssd_device_batch), P]
@@ -167,6 +178,10 @@ def dssd_set_fused_limit(ctx, max_blocks):
 def dssd_random_words(ctx, seed, step, session_first, position_first, n_sessions, n_positions, words_ptr, stream):
     return load().dssd_random_words(ctx, seed, step, session_first, position_first, n_sessions, n_positions,
                                     words_ptr, stream)
+
+
+def dssd_step_topk(ctx, batch, out, stream=0, check=True):
+    return _call("dssd_step_topk", ctx, batch, out, stream, check)
 
 
 def dssd_set_early_exit_schedule(ctx, begin):

@@ -13,6 +13,7 @@
 #include "dssd_fused_kernels.hpp"
 #include "dssd_util_kernels.hpp"
 #include "dssd_lazy_kernels.hpp"
+#include "dssd_topk_kernels.hpp"
 #include "dssd_split_kernels.hpp"
 
 using namespace dssd;
@@ -80,7 +81,7 @@ extern "C" const char* dssd_kernel_name(int k) {
   static const char* names[DSSD_K_COUNT] = {"row_chunk_stats", "accept_scan", "resid_mass", "resid_pick",
                                             "bonus_pick", "export_p_rows", "device_resid_mass",
                                             "device_resid_pick", "fused_small_step", "read_probe",
-                                            "row_chunk_stats_block"};
+                                            "row_chunk_stats_block", "topk_step"};
   return (k >= 0 && k < DSSD_K_COUNT) ? names[k] : "?";
 }
 
@@ -550,6 +551,37 @@ extern "C" dssd_status dssd_probe_read(dssd_ctx* c, const void* buf, size_t byte
     Timed t(c, DSSD_K_READ_PROBE, s);
     hipLaunchKernelGGL(read_probe, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, s,
                        static_cast<const u32x4*>(buf), chunks, reinterpret_cast<uint32_t*>(c->resid_mass));
+  }
+  return launch_status();
+}
+
+extern "C" dssd_status dssd_step_topk(dssd_ctx* c, const dssd_topk_batch* b, dssd_out* o, void* hip_stream) {
+  if (!c || !b || !o) return DSSD_EINVAL;
+  if (b->B < 0 || b->k < 1 || b->k > kWave || b->gamma < 0 || b->V < 0 || b->total_drafts < 0) return DSSD_EINVAL;
+  if (!b->draft_offsets && b->total_drafts != (int64_t)b->B * b->gamma) return DSSD_EINVAL;
+  if (b->B == 0) return DSSD_OK;
+  if (!b->p_idx || !b->p_logit || !o->accepted_len || !o->rejected || !o->out_token) return DSSD_EINVAL;
+  if (b->total_drafts > 0 && (!b->q_idx || !b->q_prob || !b->draft_tokens)) return DSSD_EINVAL;
+  auto mis = [](const void* p, uintptr_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) != 0; };
+  if (mis(b->draft_offsets, 4) || mis(b->p_idx, 4) || mis(b->p_logit, 4) || mis(b->q_idx, 4) || mis(b->q_prob, 4) ||
+      mis(b->draft_tokens, 4) || mis(b->inv_temperature, 4) || mis(b->step_counter, 8) || mis(o->accepted_len, 4) ||
+      mis(o->rejected, 4) || mis(o->out_token, 4) || mis(o->row_stats, 4) || mis(o->p_tok, 4) || mis(o->q_tok, 4) ||
+      mis(o->status, 4))
+    return DSSD_EALIGN;
+  if ((b->B + 3) / 4 > 0x7FFFFFFF) return DSSD_EUNSUPPORTED;
+  TopkView t;
+  t.B = b->B; t.k = b->k; t.gamma = b->gamma; t.V = b->V; t.R_Q = b->total_drafts;
+  t.offsets = b->draft_offsets; t.p_idx = b->p_idx; t.p_logit = b->p_logit; t.q_idx = b->q_idx; t.q_prob = b->q_prob;
+  t.tokens = b->draft_tokens; t.inv_temp = b->inv_temperature;
+  t.seed_lo = (uint32_t)b->seed; t.seed_hi = (uint32_t)(b->seed >> 32);
+  t.step_lo = (uint32_t)b->step; t.step_hi = (uint32_t)(b->step >> 32);
+  t.session_base = b->session_base; t.step_dev = b->step_counter;
+  t.accepted_len = o->accepted_len; t.rejected = o->rejected; t.out_token = o->out_token;
+  t.row_stats = o->row_stats; t.p_tok = o->p_tok; t.q_tok = o->q_tok; t.status = o->status;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  {
+    Timed tm(c, DSSD_K_TOPK_STEP, s);
+    DSSD_LAUNCH(topk_step, (b->B + 3) / 4, s, t);
   }
   return launch_status();
 }
