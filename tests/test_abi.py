@@ -40,6 +40,8 @@ def test_struct_layout_matches_the_header(tmp_path):
                    ' offsetof(dssd_device_batch, p_rows), offsetof(dssd_device_batch, seed),'
                    ' offsetof(dssd_device_batch, out_token), offsetof(dssd_device_batch, status));'
                    'printf("%zu %zu\\n", offsetof(dssd_batch, step_counter), offsetof(dssd_device_batch, step_counter));'
+                   'printf("%zu %zu %zu %zu %zu\\n", sizeof(dssd_topk_batch), offsetof(dssd_topk_batch, total_drafts),'
+                   ' offsetof(dssd_topk_batch, q_prob), offsetof(dssd_topk_batch, seed), offsetof(dssd_topk_batch, step_counter));'
                    'return 0;}\n')
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
@@ -51,7 +53,9 @@ def test_struct_layout_matches_the_header(tmp_path):
             D.dssd_batch.draft_q_tok.offset, C.sizeof(D.dssd_device_batch), D.dssd_device_batch.p_rows.offset,
             D.dssd_device_batch.seed.offset, D.dssd_device_batch.out_token.offset,
             D.dssd_device_batch.status.offset,
-            D.dssd_batch.step_counter.offset, D.dssd_device_batch.step_counter.offset]
+            D.dssd_batch.step_counter.offset, D.dssd_device_batch.step_counter.offset,
+            C.sizeof(D.dssd_topk_batch), D.dssd_topk_batch.total_drafts.offset, D.dssd_topk_batch.q_prob.offset,
+            D.dssd_topk_batch.seed.offset, D.dssd_topk_batch.step_counter.offset]
     assert got == want
 
 
@@ -66,6 +70,7 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert D.load().dssd_set_fused_pair_limit(None, 1) == D.DSSD_EINVAL
     assert D.load().dssd_set_early_exit_schedule(None, None, 0) == D.DSSD_EINVAL
     assert D.load().dssd_random_words(None, 0, 0, 0, 0, 1, 1, None, None) == D.DSSD_EINVAL
+    assert D.load().dssd_step_topk(None, None, None, None) == D.DSSD_EINVAL
     assert D.status_str(D.DSSD_EALIGN) == "misaligned pointer"
     assert D.kernel_name(D.K_ROW_STATS) == "row_chunk_stats"
     assert D.dssd_workspace_bytes(0, 10) == 0 and D.dssd_workspace_bytes(100, 32000) > 100 * 16 * 8
