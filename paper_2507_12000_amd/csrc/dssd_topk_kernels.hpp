@@ -9,7 +9,7 @@
 //   elsewhere; inverse CDF in vocabulary order, as everywhere in this library;
 //   bonus token from P_gamma if every draft was accepted.
 // One wave per session, lane = list entry, the whole step in one launch; a session's rows are
-// read only as far as its first rejection.
+// read only as far as its first rejection (plus one row fetched ahead).
 #pragma once
 #include "dssd_kernels.hpp"
 
@@ -70,12 +70,30 @@ __global__ __launch_bounds__(256) void topk_step(const TopkView t) {
   const bool in_list = lane < t.k;
   int32_t first_reject = g, token = -1, last = -1;
   if (!bad) {
+    // one position ahead: the lists of position i + 1 are asked for before position i is decided,
+    // so that their latency runs under the arithmetic (at most one row is fetched in vain)
+    struct Lists { int32_t idx; float z; int32_t x, qi; float qp; };
+    auto fetch = [&](int32_t i) {
+      Lists L{-1, 0.f, 0, -1, 0.f};
+      if (i > g) return L;
+      const int64_t row = lrow0 + i;
+      if (in_list) { L.idx = t.p_idx[row * t.k + lane]; L.z = t.p_logit[row * t.k + lane]; }
+      if (i < g) {
+        const int64_t qrow = off0 + i;
+        L.x = t.tokens[qrow];
+        if (in_list) { L.qi = t.q_idx[qrow * t.k + lane]; L.qp = t.q_prob[qrow * t.k + lane]; }
+      }
+      return L;
+    };
+    Lists next = fetch(0);
     for (int32_t i = 0; i <= g; ++i) {
       last = i;
+      const Lists cur = next;
+      next = fetch(i + 1);
       const int64_t row = lrow0 + i;
-      const int32_t idx = in_list ? t.p_idx[row * t.k + lane] : -1;
+      const int32_t idx = cur.idx;
       const bool live = idx >= 0;
-      const float z = live ? t.p_logit[row * t.k + lane] : neg_inf();
+      const float z = live ? cur.z : neg_inf();
       const float M2 = wave_max(live ? z * c1 : neg_inf());
       const float e = (M2 > neg_inf()) ? fast_exp2(fmaf(z, c1, -M2)) : 0.f;   // 0 for unused entries
       const float Z = wave_sum(live ? e : 0.f);
@@ -91,9 +109,9 @@ __global__ __launch_bounds__(256) void topk_step(const TopkView t) {
         break;
       }
       const int64_t qrow = off0 + i;
-      const int32_t x = t.tokens[qrow];
-      const int32_t qi = in_list ? t.q_idx[qrow * t.k + lane] : -1;
-      const float qp = qi >= 0 ? t.q_prob[qrow * t.k + lane] : 0.f;
+      const int32_t x = cur.x;
+      const int32_t qi = cur.qi;
+      const float qp = qi >= 0 ? cur.qp : 0.f;
       if (x < 0 || (t.V > 0 && x >= t.V)) {
         bad |= 1;
         if (lane == 0) {
