@@ -901,3 +901,38 @@ def test_early_exit_never_touches_rows_after_the_stopping_block(ctx):
         assert (clean[key] == t[key].cpu().numpy()).all(), key
     full = gpu_step(ctx, poisoned, 8, 2)
     assert all(full["status"][b] & D.SESSION_BAD_ROW for b in hit)
+
+
+def test_early_exit_rounds_inside_a_hip_graph(ctx):
+    """The early-exit rounds have host-fixed grids and clear their list lengths in a kernel, so
+    they record into a graph like the other calls; with the device-resident step counter every
+    replay equals the eager default path at that step."""
+    w = synth.Workload("graph_ee", B=64, V=30000, gamma=0, dtype="bf16", gamma_range=(1, 10),
+                       sigmas=(0.5, 1.5), frac_q_equals_p=0.2)
+    inputs = synth.generate(w, seed=19, device=DEV)
+    counter = torch.zeros(1, dtype=torch.int64, device=DEV)
+    batch = D.make_batch(inputs, seed=6, step=100, step_counter=counter, flags=D.FLAG_EARLY_EXIT)
+    t, out = D.alloc_out(inputs, DEV)
+    D.dssd_set_early_exit_schedule(ctx.handle, (0, 2, 5))
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            ctx.step_fused(batch, out)                # warm-up on the capture stream
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                ctx.step_fused(batch, out)
+                counter.add_(1)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            for v in t.values():
+                v.fill_(-3)
+            graph.replay()
+            torch.cuda.synchronize()
+            got = {k: v.cpu().numpy().copy() for k, v in t.items()}
+            want = gpu_step(ctx, inputs, 6, 100 + rep)       # eager default path in between
+            for k in ("accepted_len", "rejected", "out_token", "status"):
+                assert (got[k] == want[k]).all(), (k, rep)
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
