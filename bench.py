@@ -438,6 +438,18 @@ def main():
                      "traffic": traffic, "algorithmic_bytes_per_launch": dom_bytes,
                      "avg_launch_us": k1_us},
     }
+    # The paper's communication model (Sec. 2.2, 3.1) fed with what this step measured: the share
+    # of sessions with a rejection is its indicator a.  Link as in Table 1: T_NTT = 20 ms and 8 ms
+    # to move one vocabulary distribution (so the rate scales with this workload's V at 16 bit).
+    from paper_2507_12000_amd import latency_model as LM
+    rate = LM.distribution_bits(w.V, 16) / 8e-3
+    link = LM.Link(t_ntt=20e-3, rate_up=rate, rate_down=rate)
+    mean_gamma = inputs["R_Q"] / max(w.B, 1)
+    result["paper_comm_model"] = {
+        "link": "T_NTT 20 ms, 8 ms per vocabulary distribution at 16 bit (Table 1's setting)",
+        "mean_gamma": mean_gamma, "rejected_share": float(rejected.mean()),
+        "dsd_comm_ms": 1e3 * (mean_gamma * LM.distribution_bits(w.V, 16) / link.rate_up + link.t_ntt),
+        "dssd_comm_ms": 1e3 * LM.dssd_comm_time_from_flags(rejected.tolist(), w.V, 16, link)}
     # read ceiling of this chip for the statistics kernel's access pattern, over the same buffer
     lg = inputs["logits"]
     nbytes = lg.numel() * lg.element_size()
