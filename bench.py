@@ -280,7 +280,8 @@ def main():
     ap.add_argument("--split", action="store_true",
                     help="also time the edge/device split path (q scalars up, fp16 P rows down)")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default 200; 1000 for --config 0, whose step is a few microseconds)")
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="index into the five benchmark workloads")
     ap.add_argument("--seed", type=int, default=0)
@@ -291,6 +292,8 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain device copy of known size instead (calibrates the HBM byte counters)")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 1000 if args.config == 0 else 200
     if args.gpus != 1:
         print("bench.py measures one GPU: the verification step shards by session with no "
               "collective, and no multi-GPU run is part of this benchmark (use --gpus 1).", file=sys.stderr)
