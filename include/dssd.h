@@ -36,7 +36,7 @@
 extern "C" {
 #endif
 
-typedef struct dssd_ctx dssd_ctx; /* opaque: device workspace + profiling events */
+typedef struct dssd_ctx dssd_ctx; /* opaque: device workspace, settings, timing events */
 
 typedef enum { DSSD_F32 = 0, DSSD_BF16 = 1, DSSD_F16 = 2 /* IEEE binary16: downlink P rows only */ } dssd_dtype;
 
@@ -168,25 +168,13 @@ dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *
 /* The whole step in one call, as in Algorithm 1 where the edge does all of it: equivalent to
  * dssd_verify_batch, dssd_residual_sample, dssd_bonus_sample in a row on the same stream, with
  * bit-identical outputs.  Batches with uniform gamma (draft_offsets == NULL) whose grid is small
- * (at most the limit set by dssd_set_fused_limit workgroups, default 512) and whose rows are
+ * (at most 512 workgroups unless dssd_set_fused_limit of dssd_aux.h says otherwise) and whose rows are
  * short (V * (logit bytes + 4) <= 384 KiB) run as ONE kernel launch, which is what matters when
  * a step is bound by launch latency rather than bandwidth; small grids with longer rows run as
  * TWO launches (statistics + accept + bonus, then the redraw of rejected sessions); all others
  * run the kernels of the three calls, with the bonus draw folded into the accept launch when
  * the rows are dense (one launch fewer).  Needs the full Q rows (draft_probs). */
 dssd_status dssd_step_fused(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
-/* Largest grid (workgroups = B * ceil((gamma+1) * chunks_per_row / 4)) that dssd_step_fused runs
- * as a single launch; 0 disables the single-launch path; a negative value sets the limit to its
- * magnitude and lifts the row-length rule (for tests and measurements). */
-dssd_status dssd_set_fused_limit(dssd_ctx *ctx, int64_t max_blocks);
-/* Blocks of DSSD_FLAG_EARLY_EXIT: begin[0..n) are the first rows of the blocks, strictly
- * increasing from begin[0] = 0, the last block open-ended; n in [2, 8] (one block would be the
- * default path).  n = 0 returns to the automatic choice by batch size. */
-dssd_status dssd_set_early_exit_schedule(dssd_ctx *ctx, const int32_t *begin, int32_t n);
-/* Largest grid that dssd_step_fused runs as two launches when the single-launch rule does not
- * apply; 0 disables the two-launch path.  Negative values are DSSD_EINVAL. */
-dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
-
 /* Edge side, Algorithm 2 "Downlink Transmission": after dssd_verify_batch, for every session
  * with rejected = 1 write the distribution at the rejected position, P_n(v) for v in [0, V), into
  * p_rows[b*V + v] as b_prob-bit values: p_dtype = DSSD_F32 (b_prob = 32) or DSSD_F16 (b_prob = 16,
@@ -223,28 +211,6 @@ dssd_status dssd_residual_sample_from_p(dssd_ctx *ctx, const dssd_device_batch *
 
 const char *dssd_status_str(dssd_status s);
 
-/* Kernel timing (measurement aid, not on the hot path).  Bit k of kernel_mask brackets every
- * launch of kernel k with HIP events on the launch stream (0 = off).  Each bracket costs a few
- * microseconds of queue time, so time only the kernels a measurement needs.  Kernel ids: 0 row softmax statistics,
- * 1 accept / first-reject, 2 residual chunk masses (for small batches also the pick, in one
- * launch), 3 residual pick, 4 bonus pick, 5 export of P rows, 6 and 7 chunk masses and pick of
- * the device-side redraw, 8 the single-launch step of dssd_step_fused, 9 the read probe. */
-enum { DSSD_K_ROW_STATS = 0, DSSD_K_ACCEPT = 1, DSSD_K_RESID_MASS = 2, DSSD_K_RESID_PICK = 3,
-       DSSD_K_BONUS_PICK = 4, DSSD_K_EXPORT_P = 5, DSSD_K_DEVICE_MASS = 6, DSSD_K_DEVICE_PICK = 7,
-       DSSD_K_FUSED_STEP = 8, DSSD_K_READ_PROBE = 9, DSSD_K_ROW_STATS_BLOCK = 10, DSSD_K_TOPK_STEP = 11,
-       DSSD_K_COUNT = 12 };
-dssd_status dssd_profile_enable(dssd_ctx *ctx, uint32_t kernel_mask);
-/* Synchronises the recorded events, returns the summed duration (ms) and number of launches
- * of one kernel since the last reset. */
-dssd_status dssd_profile_read(dssd_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
-dssd_status dssd_profile_reset(dssd_ctx *ctx);
-const char *dssd_kernel_name(int kernel_id);
-
-/* Measurement aid: read `bytes` (rounded down to 8 KiB) of device memory at `buf` (16-byte
- * aligned) with the access pattern of the row-statistics kernel and no arithmetic.  Its rate is
- * the read ceiling that kernel can be held against on the chip at hand. */
-dssd_status dssd_probe_read(dssd_ctx *ctx, const void *buf, size_t bytes, void *hip_stream);
-
 /* The step on top-k lists (the paper's experiments sample with top-k = 10, Sec. 4): both models'
  * rows arrive as k (token id, value) pairs instead of V values.  It computes what the dense step
  * computes on rows that are -inf (target logits) / 0 (draft probabilities) outside the lists:
@@ -272,15 +238,6 @@ typedef struct {
   const uint64_t *step_counter; /* device or NULL: as in dssd_batch                                */
 } dssd_topk_batch;
 dssd_status dssd_step_topk(dssd_ctx *ctx, const dssd_topk_batch *batch, dssd_out *out, void *hip_stream);
-
-/* Checking aid: the Philox4x32-10 blocks the step draws from, for the rectangle of sessions
- * [session_first, +n_sessions) x positions [position_first, +n_positions) (32-bit wrap-around),
- * counter = (session_base + b, position, step low, step high), key = (seed low, seed high).
- * words (device, 4-byte aligned) receives n_sessions * n_positions * 4 uint32: word 0 feeds the
- * accept test r_j of Algorithm 2, word 1 the redraw, word 2 the bonus draw, word 3 is unused. */
-dssd_status dssd_random_words(dssd_ctx *ctx, uint64_t seed, uint64_t step, uint32_t session_first,
-                              uint32_t position_first, int32_t n_sessions, int32_t n_positions,
-                              uint32_t *words, void *hip_stream);
 
 #ifdef __cplusplus
 }

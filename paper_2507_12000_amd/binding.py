@@ -1,4 +1,4 @@
-"""ctypes binding of libdssd.so (include/dssd.h).  Argument marshalling only: every step of
+"""ctypes binding of libdssd.so (include/dssd.h, include/dssd_aux.h).  Argument marshalling only: every step of
 the verification path runs in the library's HIP kernels.  PyTorch tensors are used for device
 memory and the launch stream, nothing else.  There is no CPU fallback: if the library is not
 built, or no GPU is present, the calls raise.
@@ -19,7 +19,7 @@ MAX_SUPPORT = 64
 K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
 K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_ROW_STATS_BLOCK, K_TOPK_STEP, K_COUNT = 5, 6, 7, 8, 9, 10, 11, 12
 
-# every symbol include/dssd.h declares
+# every symbol include/dssd.h and include/dssd_aux.h declare
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
            "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_step_topk", "dssd_status_str", "dssd_profile_enable",

@@ -1,6 +1,6 @@
-// C ABI of the DSSD verification library (see include/dssd.h): argument checks, workspace,
+// C ABI of the DSSD verification library (see include/dssd.h, include/dssd_aux.h): argument checks, workspace,
 // kernel launches, optional per-kernel event timing.  No step of the method runs on the host.
-#include "../../include/dssd.h"
+#include "../../include/dssd_aux.h"
 
 #include <hip/hip_runtime.h>
 
@@ -8,7 +8,6 @@
 #include <cmath>
 #include <new>
 #include <type_traits>
-#include <vector>
 
 #include "dssd_fused_kernels.hpp"
 #include "dssd_util_kernels.hpp"
@@ -22,6 +21,8 @@ static_assert(kMaxSupport == DSSD_MAX_SUPPORT, "header and kernels must agree on
 
 struct dssd_ctx {
   int device = 0;
+  int32_t xcds = 8;                  // XCDs of the device, read at creation
+  int32_t cus = 256;                 // compute units of the device
   int64_t max_rows = 0;
   int32_t max_V = 0;
   int32_t max_C = 0;
@@ -45,9 +46,15 @@ struct dssd_ctx {
   bool fused_force = false;          // set by dssd_set_fused_limit with a negative limit: ignore the row-size rule
   int64_t fused_max_blocks = 512;    // dssd_step_fused: largest grid that runs as one launch
   int64_t pair_max_blocks = 512;     // dssd_step_fused: largest grid that runs as two launches
-  std::vector<hipEvent_t> ev_begin[DSSD_K_COUNT], ev_end[DSSD_K_COUNT];
+  // Timing brackets: a fixed pool of event pairs per kernel, created by dssd_profile_enable.
+  hipEvent_t* ev_begin[DSSD_K_COUNT] = {};
+  hipEvent_t* ev_end[DSSD_K_COUNT] = {};
+  size_t ev_cap[DSSD_K_COUNT] = {};
   size_t ev_used[DSSD_K_COUNT] = {};
+  size_t ev_dropped[DSSD_K_COUNT] = {};   // brackets skipped because the pool was exhausted
+  bool ev_failed = false;                  // an event could not be recorded: the next hot call reports it
 };
+constexpr size_t kEventPool = 2048;        // brackets per kernel between two resets
 
 static inline int32_t chunks_per_row(int32_t V, int32_t dtype) {
   const int32_t ce = dtype == DSSD_BF16 ? chunk_elems<true>() : chunk_elems<false>();
@@ -90,10 +97,19 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   *out = nullptr;
   int count = 0;
   if (hipGetDeviceCount(&count) != hipSuccess || device >= count) return DSSD_EHIP;
+  int previous = -1;
+  if (hipGetDevice(&previous) != hipSuccess) previous = -1;
   if (hipSetDevice(device) != hipSuccess) return DSSD_EHIP;
+  // the caller's current device is put back on every way out
+  struct Restore { int d; ~Restore() { if (d >= 0) (void)hipSetDevice(d); } } restore{previous};
   dssd_ctx* c = new (std::nothrow) dssd_ctx;
   if (!c) return DSSD_ENOMEM;
   c->device = device;
+  int attr = 0;
+  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeNumberOfXccs, device) == hipSuccess && attr >= 1) c->xcds = attr;
+  else (void)hipGetLastError();
+  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && attr >= 1) c->cus = attr;
+  else (void)hipGetLastError();
   c->max_rows = max_rows;
   c->max_V = max_V;
   c->max_C = chunks_per_row(max_V, DSSD_F32);  // fp32 chunks hold fewer elements: the larger count
@@ -133,8 +149,12 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
 extern "C" void dssd_destroy(dssd_ctx* c) {
   if (!c) return;
   for (int k = 0; k < DSSD_K_COUNT; ++k) {
-    for (hipEvent_t e : c->ev_begin[k]) (void)hipEventDestroy(e);
-    for (hipEvent_t e : c->ev_end[k]) (void)hipEventDestroy(e);
+    for (size_t i = 0; i < c->ev_cap[k]; ++i) {
+      (void)hipEventDestroy(c->ev_begin[k][i]);
+      (void)hipEventDestroy(c->ev_end[k][i]);
+    }
+    delete[] c->ev_begin[k];
+    delete[] c->ev_end[k];
   }
   if (c->workspace) (void)hipFree(c->workspace);
   delete c;
@@ -165,7 +185,7 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   const int64_t R_L = b->total_drafts + b->B;
   const int32_t C = chunks_per_row(b->V, b->logits_dtype);
   if (R_L > c->max_rows || b->V > c->max_V || C > c->max_C) return DSSD_ENOMEM;
-  v->B = b->B; v->V = b->V; v->gamma = b->gamma; v->C = C;
+  v->B = b->B; v->V = b->V; v->gamma = b->gamma; v->C = C; v->xcds = c->xcds;
   v->R_L = R_L; v->R_Q = b->total_drafts;
   v->offsets = b->draft_offsets; v->logits = b->logits; v->draft_probs = b->draft_probs;
   v->q_scalars = b->draft_probs ? nullptr : b->draft_q_tok;   // Q rows win when both are given
@@ -190,21 +210,26 @@ static bool vector_ok(const dssd_batch* b) {
 }
 
 namespace {
+// Brackets one launch with a pair of events from the kernel's pool.  Nothing is created here:
+// a pool that is used up drops the bracket (dssd_profile_read then says so), a stream that is
+// being captured into a graph is left alone, and a record that fails is reported by the hot
+// call through launch_status(c).
 struct Timed {
-  dssd_ctx* c; int k; hipStream_t s; hipEvent_t end = nullptr; bool failed = false;
+  dssd_ctx* c; int k; hipStream_t s; hipEvent_t end = nullptr;
   Timed(dssd_ctx* c_, int k_, hipStream_t s_) : c(c_), k(k_), s(s_) {
     if (!((c->profile_mask >> k) & 1u)) return;
-    if (c->ev_used[k] == c->ev_begin[k].size()) {
-      hipEvent_t a, b;
-      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { failed = true; return; }
-      c->ev_begin[k].push_back(a);
-      c->ev_end[k].push_back(b);
-    }
-    const size_t i = c->ev_used[k]++;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); c->ev_failed = true; return; }
+    if (cap != hipStreamCaptureStatusNone) return;
+    if (c->ev_used[k] >= c->ev_cap[k]) { ++c->ev_dropped[k]; return; }
+    const size_t i = c->ev_used[k];
+    if (hipEventRecord(c->ev_begin[k][i], s) != hipSuccess) { (void)hipGetLastError(); c->ev_failed = true; return; }
+    ++c->ev_used[k];
     end = c->ev_end[k][i];
-    if (hipEventRecord(c->ev_begin[k][i], s) != hipSuccess) failed = true;
   }
-  ~Timed() { if (end) (void)hipEventRecord(end, s); }
+  ~Timed() {
+    if (end && hipEventRecord(end, s) != hipSuccess) { (void)hipGetLastError(); c->ev_failed = true; }
+  }
 };
 }  // namespace
 
@@ -213,7 +238,10 @@ struct Timed {
     hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(256), 0, stream, __VA_ARGS__); \
   } while (0)
 
-static dssd_status launch_status() { return hipGetLastError() == hipSuccess ? DSSD_OK : DSSD_EHIP; }
+static dssd_status launch_status(const dssd_ctx* c) {
+  const bool launched = hipGetLastError() == hipSuccess;
+  return launched && !c->ev_failed ? DSSD_OK : DSSD_EHIP;
+}
 
 // Run-time booleans to template arguments: f receives one std::bool_constant per flag, in order.
 // FLAG(x) is the compile-time value of such an argument.
@@ -292,7 +320,7 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
         // the rows listed by the accept launch before: at most every row that is left
         const int64_t rows_left = b->draft_offsets ? v.R_L : (int64_t)b->B * (known_rows - begin);
         const int64_t worst = last ? rows_left : std::min<int64_t>(rows_left, (int64_t)b->B * (end - begin));
-        const int64_t blocks = (std::min<int64_t>((worst * v.C + 3) / 4, 1 << 16) + 7) / 8 * 8;
+        const int64_t blocks = (std::min<int64_t>((worst * v.C + 3) / 4, 1 << 16) + c->xcds - 1) / c->xcds * c->xcds;
         const RowTask* rows = c->open_rows[r & 1];
         with_flags([&](auto BF, auto AL, auto SP) {
           DSSD_LAUNCH((row_chunk_stats_list<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, s, v, rows, c->open_count + r);
@@ -314,7 +342,7 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
     }
     if (last) break;
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 // Row statistics, then accept / first-reject per session.  tail_bonus: the accept kernel also
@@ -346,7 +374,7 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
     else
       with_flags([&](auto BF) { DSSD_LAUNCH((accept_scan<FLAG(BF)>), g2, s, v); }, bf16);
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_verify_batch(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
@@ -368,7 +396,7 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
     Timed t(c, DSSD_K_RESID_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     with_flags([&](auto BF) { DSSD_LAUNCH((pick_sparse<FLAG(BF), true>), g2, s, v); }, bf16);
-    return launch_status();
+    return launch_status(c);
   }
   const int32_t groups = (v.C + 3) / 4;
   if ((int64_t)groups * b->B > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
@@ -386,7 +414,7 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     with_flags([&](auto BF, auto AL) { DSSD_LAUNCH((pick_token<FLAG(BF), FLAG(AL), true>), g2, s, v); }, bf16, al);
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_bonus_sample(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
@@ -399,24 +427,32 @@ extern "C" dssd_status dssd_bonus_sample(dssd_ctx* c, const dssd_batch* b, dssd_
     Timed t(c, DSSD_K_BONUS_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     with_flags([&](auto BF) { DSSD_LAUNCH((pick_sparse<FLAG(BF), false>), g2, s, v); }, bf16);
-    return launch_status();
+    return launch_status(c);
   }
   {
     Timed t(c, DSSD_K_BONUS_PICK, s);
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     with_flags([&](auto BF, auto AL) { DSSD_LAUNCH((pick_token<FLAG(BF), FLAG(AL), false>), g2, s, v); }, bf16, al);
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 // The whole step in one call: what Algorithm 1 does at the edge (accept/reject, redraw on a
 // rejection, bonus token otherwise).  Small batches with uniform gamma run as a single launch;
 // everything else is the three calls in a row.
+static dssd_status step_fused_launches(dssd_ctx* c, const dssd_batch* b, dssd_out* o, const BatchView& v,
+                                       void* hip_stream);
+
 extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_out* o, void* hip_stream) {
   BatchView v;
   const dssd_status st = check_and_view(c, b, o, &v);
   if (st != DSSD_OK || b->B == 0) return st;
   if (b->total_drafts > 0 && !b->draft_probs) return DSSD_EINVAL;
+  return step_fused_launches(c, b, o, v, hip_stream);
+}
+
+static dssd_status step_fused_launches(dssd_ctx* c, const dssd_batch* b, dssd_out* o, const BatchView& v,
+                                       void* hip_stream) {
   const int64_t groups = ((int64_t)(b->gamma + 1) * v.C + 3) / 4;
   // One launch pays only while the lone workgroup that finishes a session can stream the
   // rejected row (logits + Q) quickly: small grids and rows of a few hundred KiB.
@@ -448,10 +484,10 @@ extern "C" dssd_status dssd_step_fused(dssd_ctx* c, const dssd_batch* b, dssd_ou
     }, bf16, al, single);
   }
   if (pair && b->total_drafts > 0) {
-    const dssd_status r = launch_status();
+    const dssd_status r = launch_status(c);
     return r == DSSD_OK ? dssd_residual_sample(c, b, o, hip_stream) : r;
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_set_fused_limit(dssd_ctx* c, int64_t max_blocks) {
@@ -497,7 +533,7 @@ extern "C" dssd_status dssd_export_p_rows(dssd_ctx* c, const dssd_batch* b, void
       DSSD_LAUNCH((export_p_rows<FLAG(BF), FLAG(AL), FLAG(H)>), grid, s, v, groups, p_rows);
     }, bf16, al, f16);
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_device_batch* b, void* hip_stream) {
@@ -537,7 +573,7 @@ extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_devic
     const unsigned g2 = (unsigned)((b->B + 3) / 4);
     with_flags([&](auto H, auto AL) { DSSD_LAUNCH((device_pick<FLAG(H), FLAG(AL)>), g2, s, d); }, f16, al);
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_probe_read(dssd_ctx* c, const void* buf, size_t bytes, void* hip_stream) {
@@ -550,9 +586,9 @@ extern "C" dssd_status dssd_probe_read(dssd_ctx* c, const void* buf, size_t byte
   {
     Timed t(c, DSSD_K_READ_PROBE, s);
     hipLaunchKernelGGL(read_probe, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, s,
-                       static_cast<const u32x4*>(buf), chunks, reinterpret_cast<uint32_t*>(c->resid_mass));
+                       static_cast<const u32x4*>(buf), chunks, reinterpret_cast<uint32_t*>(c->resid_mass), c->xcds);
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_step_topk(dssd_ctx* c, const dssd_topk_batch* b, dssd_out* o, void* hip_stream) {
@@ -583,7 +619,7 @@ extern "C" dssd_status dssd_step_topk(dssd_ctx* c, const dssd_topk_batch* b, dss
     Timed tm(c, DSSD_K_TOPK_STEP, s);
     DSSD_LAUNCH(topk_step, (b->B + 3) / 4, s, t);
   }
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_random_words(dssd_ctx* c, uint64_t seed, uint64_t step, uint32_t session_first,
@@ -599,18 +635,39 @@ extern "C" dssd_status dssd_random_words(dssd_ctx* c, uint64_t seed, uint64_t st
                      static_cast<hipStream_t>(hip_stream), session_first, position_first, n_sessions,
                      n_positions, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t)seed, (uint32_t)(seed >> 32),
                      words);
-  return launch_status();
+  return launch_status(c);
 }
 
 extern "C" dssd_status dssd_profile_enable(dssd_ctx* c, uint32_t kernel_mask) {
   if (!c) return DSSD_EINVAL;
+  // the pools of the kernels asked for are created here, never inside a hot call
+  for (int k = 0; k < DSSD_K_COUNT; ++k) {
+    if (!((kernel_mask >> k) & 1u) || c->ev_cap[k]) continue;
+    hipEvent_t* a = new (std::nothrow) hipEvent_t[kEventPool];
+    hipEvent_t* b = new (std::nothrow) hipEvent_t[kEventPool];
+    size_t made = 0;
+    if (a && b)
+      for (; made < kEventPool; ++made) {
+        if (hipEventCreate(&a[made]) != hipSuccess) break;
+        if (hipEventCreate(&b[made]) != hipSuccess) { (void)hipEventDestroy(a[made]); break; }
+      }
+    if (made < kEventPool) {
+      (void)hipGetLastError();
+      for (size_t i = 0; i < made; ++i) { (void)hipEventDestroy(a[i]); (void)hipEventDestroy(b[i]); }
+      delete[] a;
+      delete[] b;
+      return a && b ? DSSD_EHIP : DSSD_ENOMEM;
+    }
+    c->ev_begin[k] = a; c->ev_end[k] = b; c->ev_cap[k] = kEventPool;
+  }
   c->profile_mask = kernel_mask;
   return DSSD_OK;
 }
 
 extern "C" dssd_status dssd_profile_reset(dssd_ctx* c) {
   if (!c) return DSSD_EINVAL;
-  for (int k = 0; k < DSSD_K_COUNT; ++k) c->ev_used[k] = 0;
+  for (int k = 0; k < DSSD_K_COUNT; ++k) c->ev_used[k] = c->ev_dropped[k] = 0;
+  c->ev_failed = false;
   return DSSD_OK;
 }
 
@@ -625,5 +682,6 @@ extern "C" dssd_status dssd_profile_read(dssd_ctx* c, int k, double* total_ms, i
   }
   *total_ms = sum;
   *launches = (int64_t)c->ev_used[k];
-  return DSSD_OK;
+  if (c->ev_failed) return DSSD_EHIP;
+  return c->ev_dropped[k] ? DSSD_ENOMEM : DSSD_OK;   // ENOMEM: launches beyond the pool went untimed
 }

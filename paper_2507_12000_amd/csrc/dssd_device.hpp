@@ -191,13 +191,13 @@ __device__ __forceinline__ int32_t arrive(int32_t* counter) {
   return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Consecutive workgroup ids are dealt round-robin to the chip's 8 XCDs.  This maps a hardware
-// workgroup id to a logical one so that each XCD walks one contiguous eighth of the work (and
-// of the address range) instead of every eighth block of it.
-constexpr int kXcds = 8;
-__device__ __forceinline__ int64_t xcd_contiguous(int64_t block, int64_t blocks) {
-  const int64_t per = blocks / kXcds;
-  return block < per * kXcds ? (block % kXcds) * per + block / kXcds : block;
+// Consecutive workgroup ids are dealt round-robin to the chip's XCDs (8 on MI355X; the host reads
+// the count from the device).  This maps a hardware workgroup id to a logical one so that each
+// XCD walks one contiguous share of the work (and of the address range) instead of every n-th
+// block of it.  Workgroups beyond the last full round keep their id.
+__device__ __forceinline__ int64_t xcd_contiguous(uint32_t block, uint32_t blocks, uint32_t xcds) {
+  const uint32_t per = blocks / xcds;
+  return block < per * xcds ? (int64_t)(block % xcds) * per + block / xcds : (int64_t)block;
 }
 
 }  // namespace dssd

@@ -25,6 +25,7 @@ struct __attribute__((aligned(16))) Job {
 
 struct BatchView {
   int32_t B, V, gamma, C;            // C = chunks per row
+  int32_t xcds;                      // XCDs of the device (round-robin targets of consecutive workgroups)
   int64_t R_L, R_Q;
   const int32_t* offsets;            // may be null
   const void* logits;
@@ -135,7 +136,7 @@ __device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int
 template <bool BF16, bool ALIGNED, bool SUPPORT>
 __global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
   const int lane = threadIdx.x & 63;
-  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
+  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x, a.xcds) * 4 + (threadIdx.x >> 6);
   if (task >= a.R_L * a.C) return;
   const int64_t row = task / a.C;
   const int32_t c = (int32_t)(task - row * a.C);
@@ -156,9 +157,9 @@ __global__ __launch_bounds__(256) void zero_i32(int32_t* p, int64_t n) {
 // Measurement aid: the access pattern of row_chunk_stats (one wave per 8 KiB, eight non-temporal
 // 128-bit loads per lane, XCD-contiguous block order) with no arithmetic but an OR.  What this
 // reaches is the read bandwidth the statistics kernel can be held against on a given chip.
-__global__ __launch_bounds__(256) void read_probe(const u32x4* src, int64_t chunks, uint32_t* sink) {
+__global__ __launch_bounds__(256) void read_probe(const u32x4* src, int64_t chunks, uint32_t* sink, int32_t xcds) {
   const int lane = threadIdx.x & 63;
-  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
+  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x, xcds) * 4 + (threadIdx.x >> 6);
   if (task >= chunks) return;
   const u32x4* p = src + task * kChunkVecs + lane;
   uint32_t acc = 0;

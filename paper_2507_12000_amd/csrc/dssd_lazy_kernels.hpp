@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, i
   const int lane = threadIdx.x & 63;
   if (blockIdx.x == 0 && threadIdx.x < n_zero) zero[threadIdx.x] = 0;
   const int64_t per_session = (int64_t)width * a.C;
-  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
+  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x, a.xcds) * 4 + (threadIdx.x >> 6);
   if (task >= a.B * per_session) return;
   const int32_t b = (int32_t)(task / per_session);
   const int32_t rem = (int32_t)(task - b * per_session);
@@ -70,10 +70,11 @@ __global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, c
                                                             const ListLengths* lengths) {
   const int lane = threadIdx.x & 63;
   const int64_t total = (int64_t)listed_rows(*lengths) * a.C;
-  // each XCD walks one contiguous eighth of the list (the grid is a multiple of 8 workgroups)
-  const int64_t nblk = (total + 3) / 4, per = (nblk + kXcds - 1) / kXcds;
-  const int64_t first = (int64_t)(blockIdx.x % kXcds) * per;
-  for (int64_t k = blockIdx.x / kXcds; k < per; k += gridDim.x / kXcds) {
+  // each XCD walks one contiguous share of the list (the grid is a multiple of the XCD count)
+  const uint32_t xcds = (uint32_t)a.xcds;
+  const int64_t nblk = (total + 3) / 4, per = (nblk + xcds - 1) / xcds;
+  const int64_t first = (int64_t)(blockIdx.x % xcds) * per;
+  for (int64_t k = blockIdx.x / xcds; k < per; k += gridDim.x / xcds) {
     const int64_t task = (first + k) * 4 + (threadIdx.x >> 6);
     if (task >= total) continue;
     const int64_t e = task / a.C;
