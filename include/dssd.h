@@ -175,6 +175,28 @@ dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *
  * run the kernels of the three calls, with the bonus draw folded into the accept launch when
  * the rows are dense (one launch fewer).  Needs the full Q rows (draft_probs). */
 dssd_status dssd_step_fused(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
+/* The whole step for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and bit-identical
+ * results as dssd_step_fused, but it takes no context: the workspace (chunk statistics, chunk
+ * masses, per-session job records, arrival counters) is a static device array of
+ * DSSD_STATIC_SCRATCH_BYTES that is part of the library's code object, so every GPU the library
+ * runs on holds it until the process ends.  The call allocates and frees nothing, on the host or
+ * on the device, and does not synchronise.
+ *   - The current HIP device must be the one `hip_stream` and every buffer belong to.
+ *   - A batch needs 8 bytes per chunk of every logits row (a chunk is 8 KiB of logits: 4096 bf16
+ *     or 2048 fp32 entries) plus about 48 bytes per session and 4 bytes per session and chunk;
+ *     one that needs more than DSSD_STATIC_SCRATCH_BYTES is refused with DSSD_ENOMEM before
+ *     anything is launched (the five benchmark workloads fit: the largest, 9 705 bf16 rows of
+ *     256 000 entries, takes 5.2 MB).
+ *   - batch->flags must be 0 (DSSD_EUNSUPPORTED otherwise: both modes keep lists elsewhere).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ *     (different streams or threads) race.  Calls in stream order on one stream are fine; the
+ *     array keeps the last call's contents and the call clears what it needs cleared.
+ *   - The first call on a device looks the array's address up (no allocation); dssd_create on
+ *     that device does it too, so either may come first. */
+#define DSSD_STATIC_SCRATCH_BYTES (8u << 20)
+dssd_status dssd_step_static(const dssd_batch *batch, dssd_out *out, void *hip_stream);
+
 /* Edge side, Algorithm 2 "Downlink Transmission": after dssd_verify_batch, for every session
  * with rejected = 1 write the distribution at the rejected position, P_n(v) for v in [0, V), into
  * p_rows[b*V + v] as b_prob-bit values: p_dtype = DSSD_F32 (b_prob = 32) or DSSD_F16 (b_prob = 16,

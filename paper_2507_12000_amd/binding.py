@@ -16,13 +16,14 @@ SESSION_SUPPORT_OVERFLOW = 16
 FLAG_SPARSE_SUPPORT = 1
 FLAG_EARLY_EXIT = 2
 MAX_SUPPORT = 64
+STATIC_SCRATCH_BYTES = 8 << 20
 K_ROW_STATS, K_ACCEPT, K_RESID_MASS, K_RESID_PICK, K_BONUS_PICK = 0, 1, 2, 3, 4
 K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_ROW_STATS_BLOCK, K_TOPK_STEP, K_COUNT = 5, 6, 7, 8, 9, 10, 11, 12
 
 # every symbol include/dssd.h and include/dssd_aux.h declare
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
-           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_step_topk", "dssd_status_str", "dssd_profile_enable",
+           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_step_static", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_step_topk", "dssd_status_str", "dssd_profile_enable",
            "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name", "dssd_probe_read")
 
 
@@ -101,6 +102,8 @@ def load():
         f = getattr(L, name)
         f.argtypes = [P, C.POINTER(dssd_batch), C.POINTER(dssd_out), P]
         f.restype = C.c_int
+    L.dssd_step_static.argtypes = [C.POINTER(dssd_batch), C.POINTER(dssd_out), P]
+    L.dssd_step_static.restype = C.c_int
     L.dssd_step_topk.argtypes = [P, C.POINTER(dssd_topk_batch), C.POINTER(dssd_out), P]
     L.dssd_step_topk.restype = C.c_int
     L.dssd_export_p_rows.argtypes = [P, C.POINTER(dssd_batch), P, C.c_int32, P]
@@ -169,6 +172,14 @@ def dssd_bonus_sample(ctx, batch, out, stream=0, check=True):
 
 def dssd_step_fused(ctx, batch, out, stream=0, check=True):
     return _call("dssd_step_fused", ctx, batch, out, stream, check)
+
+
+def dssd_step_static(batch, out, stream=0, check=True):
+    rc = load().dssd_step_static(C.byref(batch) if batch is not None else None,
+                                 C.byref(out) if out is not None else None, C.c_void_p(stream or 0))
+    if check and rc != DSSD_OK:
+        raise DssdError(rc, "dssd_step_static")
+    return rc
 
 
 def dssd_set_fused_limit(ctx, max_blocks):

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <type_traits>
 
@@ -18,6 +19,41 @@
 using namespace dssd;
 
 static_assert(kMaxSupport == DSSD_MAX_SUPPORT, "header and kernels must agree on the support size");
+
+// Workspace of dssd_step_static: one array per device, part of the loaded code object, so the
+// call never has to allocate.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address it yields (one per device) is what kernels and
+// copies receive.
+static __device__ __align__(256) unsigned char scratch[DSSD_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_lock;
+void* scratch_ptr[kMaxDevices] = {};      // device address of device d's copy of `scratch`, once resolved
+int32_t scratch_xcds[kMaxDevices] = {};   // and that device's XCD count
+
+// Address of the CURRENT device's copy of `scratch`, resolved on the first request per device.
+dssd_status current_scratch(void** ptr, int32_t* xcds) {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) { (void)hipGetLastError(); return DSSD_EHIP; }
+  if (device < 0 || device >= kMaxDevices) return DSSD_EUNSUPPORTED;
+  std::lock_guard<std::mutex> hold(scratch_lock);
+  if (!scratch_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return DSSD_EHIP; }
+    int attr = 0;
+    if (hipDeviceGetAttribute(&attr, hipDeviceAttributeNumberOfXccs, device) != hipSuccess || attr < 1) {
+      (void)hipGetLastError();
+      attr = 8;
+    }
+    scratch_xcds[device] = attr;
+    scratch_ptr[device] = p;
+  }
+  *ptr = scratch_ptr[device];
+  *xcds = scratch_xcds[device];
+  return DSSD_OK;
+}
+}  // namespace
 
 struct dssd_ctx {
   int device = 0;
@@ -141,6 +177,11 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
     (void)hipFree(c->workspace);
     delete c;
     return DSSD_EHIP;
+  }
+  {   // the static scratch of this device is resolved here too, so that a later dssd_step_static
+      // on it has nothing left to set up (a failure only matters to that call, which repeats it)
+    void* p; int32_t x;
+    (void)current_scratch(&p, &x);
   }
   *out = c;
   return DSSD_OK;
@@ -488,6 +529,52 @@ static dssd_status step_fused_launches(dssd_ctx* c, const dssd_batch* b, dssd_ou
     return r == DSSD_OK ? dssd_residual_sample(c, b, o, hip_stream) : r;
   }
   return launch_status(c);
+}
+
+// The whole step on the static scratch array: no context, no allocation.
+extern "C" dssd_status dssd_step_static(const dssd_batch* b, dssd_out* o, void* hip_stream) {
+  if (!b || !o) return DSSD_EINVAL;
+  if (b->B < 0 || b->V < 1 || b->gamma < 0 || b->total_drafts < 0) return DSSD_EINVAL;
+  if (b->logits_dtype != DSSD_F32 && b->logits_dtype != DSSD_BF16) return DSSD_EINVAL;
+  if (b->flags & ~(uint32_t)(DSSD_FLAG_SPARSE_SUPPORT | DSSD_FLAG_EARLY_EXIT)) return DSSD_EINVAL;
+  if (b->flags) return DSSD_EUNSUPPORTED;   // both modes need lists beyond the static scratch
+  // Carve the scratch for this batch; refuse what does not fit before anything touches the device.
+  const int32_t C = chunks_per_row(b->V, b->logits_dtype);
+  if (b->total_drafts > (int64_t)1 << 40) return DSSD_ENOMEM;
+  const size_t rows = (size_t)(b->total_drafts + b->B), B = (size_t)b->B;
+  if (rows * (size_t)C > DSSD_STATIC_SCRATCH_BYTES) return DSSD_ENOMEM;
+  const size_t at_chunk_stats = 0;
+  const size_t at_row_tab = at_chunk_stats + align256(rows * C * sizeof(float2));
+  const size_t at_resid_mass = at_row_tab + align256(rows * sizeof(float2));
+  const size_t at_resid_job = at_resid_mass + align256(B * C * sizeof(float));
+  const size_t at_bonus_job = at_resid_job + align256(B * sizeof(Job));
+  const size_t at_arrive = at_bonus_job + align256(B * sizeof(Job));
+  const size_t end = at_arrive + align256(2 * B * sizeof(int32_t));
+  if (end > DSSD_STATIC_SCRATCH_BYTES) return DSSD_ENOMEM;
+  void* base = nullptr;
+  int32_t xcds = 8;
+  const dssd_status got = current_scratch(&base, &xcds);
+  if (got != DSSD_OK) return got;
+  char* p = static_cast<char*>(base);
+  dssd_ctx c;   // a view of the scratch with the library's default settings; owns nothing
+  c.xcds = xcds;
+  c.max_rows = (int64_t)rows; c.max_V = b->V; c.max_C = C;
+  c.chunk_stats = reinterpret_cast<float2*>(p + at_chunk_stats);
+  c.row_tab = reinterpret_cast<float2*>(p + at_row_tab);
+  c.resid_mass = reinterpret_cast<float*>(p + at_resid_mass);
+  c.resid_job = reinterpret_cast<Job*>(p + at_resid_job);
+  c.bonus_job = reinterpret_cast<Job*>(p + at_bonus_job);
+  c.arrive_resid = reinterpret_cast<int32_t*>(p + at_arrive);
+  c.arrive_stats = c.arrive_resid + B;
+  BatchView v;
+  const dssd_status st = check_and_view(&c, b, o, &v);
+  if (st != DSSD_OK || b->B == 0) return st;
+  if (b->total_drafts > 0 && !b->draft_probs) return DSSD_EINVAL;
+  // The array keeps whatever the last call left, carved for another batch: the arrival
+  // counters must start at zero (a fill kernel, not a memset node, so the call can be captured).
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(zero_i32, dim3((unsigned)((2 * B + 255) / 256)), dim3(256), 0, s, c.arrive_resid, (int64_t)(2 * B));
+  return step_fused_launches(&c, b, o, v, hip_stream);
 }
 
 extern "C" dssd_status dssd_set_fused_limit(dssd_ctx* c, int64_t max_blocks) {

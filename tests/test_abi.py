@@ -80,6 +80,20 @@ def test_null_arguments_are_rejected_before_any_launch():
     assert D.load().dssd_create(None, 0, 10, 10) == D.DSSD_EINVAL
 
 
+def test_static_step_checks_its_size_limit_on_the_host():
+    """dssd_step_static refuses a batch beyond its static array before it touches a device."""
+    _built()
+    fake = 0x1000   # never dereferenced: the refusal comes first
+    out = D.dssd_out(accepted_len=fake, rejected=fake, out_token=fake)
+    big = D.dssd_batch(B=4096, V=256000, gamma=15, logits_dtype=D.DSSD_BF16, total_drafts=4096 * 15,
+                       logits=fake, draft_probs=fake, draft_tokens=fake)
+    assert D.dssd_step_static(big, out, 0, check=False) == D.DSSD_ENOMEM
+    big.flags = D.FLAG_EARLY_EXIT
+    assert D.dssd_step_static(big, out, 0, check=False) == D.DSSD_EUNSUPPORTED
+    assert D.dssd_step_static(None, out, 0, check=False) == D.DSSD_EINVAL
+    assert D.dssd_step_static(big, None, 0, check=False) == D.DSSD_EINVAL
+
+
 def test_no_cpu_fallback_without_a_gpu():
     _built()
     import torch
