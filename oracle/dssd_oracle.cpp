@@ -134,6 +134,16 @@ void dssd_oracle_softmax_row(const void* logits_row, int dtype, int32_t V, doubl
 // Step 2, one position: accept iff r < min(1, p/q), evaluated as r*q < p.
 int dssd_oracle_accept(double r, double p, double q) { return (r * q < p) ? 1 : 0; }
 
+// How far r is from the boundary of that test, in the units of r: |r - p/q| for q > 0, written
+// as |r*q - p| / q.  With q = 0 the test does not depend on r (p > 0 accepts, p = 0 rejects):
+// infinitely far, except that a p below 1e-30 counts as on the boundary, because a 32-bit
+// float evaluation may flush such a p to zero.  Used only to tell the comparison with another
+// implementation which decisions are near-ties; it takes no part in the decision.
+double dssd_oracle_accept_margin(double r, double p, double q) {
+  const double gap = std::fabs(r * q - p);
+  return q > 0.0 ? gap / q : (p > 1e-30 ? std::numeric_limits<double>::infinity() : 0.0);
+}
+
 // Probability that step 2 accepts a token whose probabilities are (p, q).
 double dssd_oracle_accept_prob(double p, double q) {
   if (q <= 0.0) return p > 0.0 ? 1.0 : 0.0;
@@ -252,9 +262,8 @@ void dssd_oracle_verify_session(const void* logits, int dtype, const float* draf
       beta[i] = b;
     }
     if (!open) continue;
-    // Step 2.  Near-tie measure in the units of r: |r*q - p| / q.
-    const double gap = std::fabs(r * q - p);
-    const double margin = q > 0.0 ? gap / q : (p > 1e-30 ? std::numeric_limits<double>::infinity() : 0.0);
+    // Step 2, and how close r came to its boundary.
+    const double margin = dssd_oracle_accept_margin(r, p, q);
     if (margin < res->accept_margin) res->accept_margin = margin;
     if (!dssd_oracle_accept(r, p, q)) {
       open = false;  // Flag = 0
@@ -398,8 +407,7 @@ void dssd_oracle_edge_session(const void* logits, int dtype, const float* q_scal
     }
     const double p = P[tokens[i]], q = (double)q_scalars[i], r = dssd_oracle_u01(words[0]);
     if (p_tok) p_tok[i] = p;
-    const double gap = std::fabs(r * q - p);
-    const double margin = q > 0.0 ? gap / q : (p > 1e-30 ? std::numeric_limits<double>::infinity() : 0.0);
+    const double margin = dssd_oracle_accept_margin(r, p, q);
     if (margin < res->accept_margin) res->accept_margin = margin;
     if (!dssd_oracle_accept(r, p, q)) {
       res->n = i;

@@ -43,6 +43,8 @@ def lib():
         L.dssd_oracle_softmax_row.restype = None
         L.dssd_oracle_accept.argtypes = [C.c_double] * 3
         L.dssd_oracle_accept.restype = C.c_int
+        L.dssd_oracle_accept_margin.argtypes = [C.c_double] * 3
+        L.dssd_oracle_accept_margin.restype = C.c_double
         L.dssd_oracle_accept_prob.argtypes = [C.c_double] * 2
         L.dssd_oracle_accept_prob.restype = C.c_double
         L.dssd_oracle_residual.argtypes = [dp, vp, C.c_int32, dp]
@@ -104,6 +106,10 @@ def softmax_row(logits_row, dtype=F32, inv_temperature=1.0):
 
 def accept(r, p, q):
     return lib().dssd_oracle_accept(float(r), float(p), float(q))
+
+
+def accept_margin(r, p, q):
+    return lib().dssd_oracle_accept_margin(float(r), float(p), float(q))
 
 
 def accept_prob(p, q):

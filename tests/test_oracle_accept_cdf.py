@@ -41,6 +41,46 @@ def test_accept_single_decisions():
     assert O.accept(0.49, 0.5, 1.0) == 1 and O.accept(0.5, 0.5, 1.0) == 0   # strict
 
 
+def test_accept_margin_hand_values():
+    """Distance of r from the accept boundary p/q, in units of r; values worked out by hand."""
+    inf = float("inf")
+    assert O.accept_margin(0.5, 0.3, 0.5) == pytest.approx(0.1, abs=1e-15)      # |0.5 - 0.6|
+    assert O.accept_margin(0.25, 0.5, 1.0) == 0.25                               # |0.25 - 0.5|
+    assert O.accept_margin(0.75, 0.25, 0.5) == 0.25                              # |0.75 - 0.5|
+    assert O.accept_margin(0.5, 0.25, 0.5) == 0.0                                # on the boundary
+    assert O.accept_margin(0.125, 0.75, 0.25) == 2.875                           # p/q = 3: far above any r
+    assert O.accept_margin(0.9, 0.2, 0.0) == inf                                 # q = 0: r plays no part
+    assert O.accept_margin(0.9, 0.0, 0.0) == 0.0 and O.accept_margin(0.1, 1e-31, 0.0) == 0.0
+    # the sign of the gap must not matter, and the unit is r (division by q, not p)
+    assert O.accept_margin(0.7, 0.3, 0.5) == pytest.approx(O.accept_margin(0.5, 0.3, 0.5), abs=1e-15)
+
+
+def test_session_accept_margin_is_the_minimum_over_the_positions_examined():
+    """A session's accept_margin covers positions 0..n (the tests Algorithm 2's loop really
+    makes) and nothing after the first rejection; recomputed here as |r - p/q| from the random
+    words and the per-position scalars."""
+    rng = np.random.default_rng(5)
+    V, gamma = 50, 6
+    seen_reject_before_end = False
+    for trial in range(40):
+        logits = rng.normal(0, 2, (gamma + 1, V)).astype(np.float32)
+        Q = rng.dirichlet(np.ones(V), gamma).astype(np.float32)
+        tokens = rng.integers(0, V, gamma).astype(np.int32)
+        o = O.verify_batch(logits, O.F32, Q, tokens, V, gamma=gamma, seed=77, step=trial, session_base=3)
+        res = o["res"][0]
+        n = int(res["n"])
+        last = min(n, gamma - 1)
+        per_pos = []
+        for i in range(last + 1):
+            r = O.u01(O.random_block(77, trial, 3, i)[0])
+            assert r == o["r_acc"][i]
+            per_pos.append(abs(r - o["p_tok"][i] / o["q_tok"][i]))
+        assert res["accept_margin"] == pytest.approx(min(per_pos), rel=1e-12, abs=1e-15)
+        if n < gamma - 1:
+            seen_reject_before_end = True
+    assert seen_reject_before_end
+
+
 WEIGHTS = [
     [0.1, 0.2, 0.3, 0.4],
     [0.0, 0.5, 0.0, 0.25, 0.25, 0.0],

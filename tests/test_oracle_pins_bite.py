@@ -36,6 +36,9 @@ MUTATIONS = {
     "u01_uses_low_bits": ("return (double)(w >> 8) * (1.0 / 16777216.0);",
                           "return (double)(w & 0xFFFFFF) * (1.0 / 16777216.0);"),
     "bonus_row_off_by_one": ("if (i == gamma) break;", "if (i == gamma - 1 && gamma > 1) break;"),
+    "margin_sign_kept": ("const double gap = std::fabs(r * q - p);", "const double gap = r * q - p;"),
+    "margin_divides_by_p": ("return q > 0.0 ? gap / q :", "return q > 0.0 ? gap / p :"),
+    "margin_counts_positions_after_the_rejection": ("    if (!open) continue;\n", ""),
     "stops_one_late": ("open = false;  // Flag = 0\n      res->n = i;",
                        "open = false;  // Flag = 0\n      res->n = i + 1 < gamma ? i + 1 : i;"),
 }
