@@ -25,6 +25,13 @@ dssd_status dssd_set_early_exit_schedule(dssd_ctx *ctx, const int32_t *begin, in
  * apply; 0 disables the two-launch path.  Negative values are DSSD_EINVAL. */
 dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
 
+/* Waves per compute unit that the two streaming kernels (row statistics; residual masses) keep
+ * resident: read throughput on this chip peaks at a moderate number of bytes in flight per unit
+ * and loses several percent towards full occupancy, so the library caps them (by requesting LDS
+ * the kernels never touch).  0 = no cap (whatever the registers allow).  Values are rounded
+ * down to whole workgroups, never below two workgroups per unit. */
+dssd_status dssd_set_stream_occupancy(dssd_ctx *ctx, int32_t stats_waves_per_cu, int32_t resid_waves_per_cu);
+
 /* ---- kernel timing ---- */
 
 /* Bit k of kernel_mask brackets every launch of kernel k with a pair of HIP events on the launch

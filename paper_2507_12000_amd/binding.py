@@ -23,7 +23,7 @@ K_EXPORT_P, K_DEVICE_MASS, K_DEVICE_PICK, K_FUSED_STEP, K_READ_PROBE, K_ROW_STAT
 # every symbol include/dssd.h and include/dssd_aux.h declare
 EXPORTS = ("dssd_workspace_bytes", "dssd_create", "dssd_destroy", "dssd_verify_batch",
            "dssd_residual_sample", "dssd_bonus_sample", "dssd_export_p_rows",
-           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_step_static", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_step_topk", "dssd_status_str", "dssd_profile_enable",
+           "dssd_residual_sample_from_p", "dssd_step_fused", "dssd_step_static", "dssd_set_fused_limit", "dssd_set_fused_pair_limit", "dssd_set_stream_occupancy", "dssd_set_early_exit_schedule", "dssd_random_words", "dssd_step_topk", "dssd_status_str", "dssd_profile_enable",
            "dssd_profile_read", "dssd_profile_reset", "dssd_kernel_name", "dssd_probe_read")
 
 
@@ -96,6 +96,8 @@ def load():
     L.dssd_random_words.restype = C.c_int
     L.dssd_set_early_exit_schedule.argtypes = [P, C.POINTER(C.c_int32), C.c_int32]
     L.dssd_set_early_exit_schedule.restype = C.c_int
+    L.dssd_set_stream_occupancy.argtypes = [P, C.c_int32, C.c_int32]
+    L.dssd_set_stream_occupancy.restype = C.c_int
     L.dssd_set_fused_pair_limit.argtypes = [P, C.c_int64]
     L.dssd_set_fused_pair_limit.restype = C.c_int
     for name in ("dssd_verify_batch", "dssd_residual_sample", "dssd_bonus_sample", "dssd_step_fused"):
@@ -199,6 +201,10 @@ def dssd_set_early_exit_schedule(ctx, begin):
     """begin: first rows of the blocks, e.g. (0, 2, 6); () returns to the automatic choice."""
     arr = (C.c_int32 * max(len(begin), 1))(*begin)
     return load().dssd_set_early_exit_schedule(ctx, arr, len(begin))
+
+
+def dssd_set_stream_occupancy(ctx, stats_waves_per_cu, resid_waves_per_cu):
+    return load().dssd_set_stream_occupancy(ctx, int(stats_waves_per_cu), int(resid_waves_per_cu))
 
 
 def dssd_set_fused_pair_limit(ctx, max_blocks):

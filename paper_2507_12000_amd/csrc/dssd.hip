@@ -59,6 +59,13 @@ struct dssd_ctx {
   int device = 0;
   int32_t xcds = 8;                  // XCDs of the device, read at creation
   int32_t cus = 256;                 // compute units of the device
+  int64_t lds_per_cu = 160 << 10;    // LDS bytes of one compute unit
+  // Streaming kernels run fastest with a moderate number of bytes in flight per compute unit
+  // (measured: read throughput peaks near 16 waves of 8 KiB and falls off by several percent
+  // towards full occupancy).  The caps below are waves per compute unit, enforced by asking for
+  // LDS the kernels never touch; 0 = whatever the registers allow.
+  int32_t stats_waves_per_cu = 12;
+  int32_t resid_waves_per_cu = 8;
   int64_t max_rows = 0;
   int32_t max_V = 0;
   int32_t max_C = 0;
@@ -146,6 +153,8 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   else (void)hipGetLastError();
   if (hipDeviceGetAttribute(&attr, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && attr >= 1) c->cus = attr;
   else (void)hipGetLastError();
+  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device) == hipSuccess && attr >= (64 << 10)) c->lds_per_cu = attr;
+  else (void)hipGetLastError();
   c->max_rows = max_rows;
   c->max_V = max_V;
   c->max_C = chunks_per_row(max_V, DSSD_F32);  // fp32 chunks hold fewer elements: the larger count
@@ -227,6 +236,9 @@ static dssd_status check_and_view(const dssd_ctx* c, const dssd_batch* b, const 
   const int32_t C = chunks_per_row(b->V, b->logits_dtype);
   if (R_L > c->max_rows || b->V > c->max_V || C > c->max_C) return DSSD_ENOMEM;
   v->B = b->B; v->V = b->V; v->gamma = b->gamma; v->C = C; v->xcds = c->xcds;
+  v->xcd_shift = -1;
+  for (int sh = 0; sh < 16; ++sh)
+    if ((1 << sh) == c->xcds) v->xcd_shift = sh;
   v->R_L = R_L; v->R_Q = b->total_drafts;
   v->offsets = b->draft_offsets; v->logits = b->logits; v->draft_probs = b->draft_probs;
   v->q_scalars = b->draft_probs ? nullptr : b->draft_q_tok;   // Q rows win when both are given
@@ -274,10 +286,22 @@ struct Timed {
 };
 }  // namespace
 
-#define DSSD_LAUNCH(kernel, grid, stream, ...)                                   \
-  do {                                                                           \
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3(256), 0, stream, __VA_ARGS__); \
+#define DSSD_LAUNCH_WG(kernel, grid, threads, lds, stream, ...)                                        \
+  do {                                                                                                 \
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(grid)), dim3((unsigned)(threads)), lds, stream, __VA_ARGS__); \
   } while (0)
+#define DSSD_LAUNCH(kernel, grid, stream, ...) DSSD_LAUNCH_WG(kernel, grid, 256, 0, stream, __VA_ARGS__)
+
+// Dynamic LDS (bytes per workgroup, never touched by the kernel) that lets at most
+// waves_per_cu / wg_waves workgroups share a compute unit: just more than an (n+1)-th of the
+// unit's LDS.  One workgroup per unit would need more than a launch may ask for: two is the floor.
+// Small grids are left alone: they are bound by latency, not by the memory system.
+static unsigned occupancy_cap_lds(const dssd_ctx* c, int wg_waves, int waves_per_cu, int64_t grid) {
+  if (waves_per_cu <= 0 || grid < (int64_t)16 * c->cus) return 0;
+  const int64_t n = std::max(waves_per_cu / wg_waves, 2);
+  const int64_t bytes = (c->lds_per_cu / (n + 1) / 512 + 1) * 512;
+  return (unsigned)std::min<int64_t>(bytes, 64 << 10);
+}
 
 static dssd_status launch_status(const dssd_ctx* c) {
   const bool launched = hipGetLastError() == hipSuccess;
@@ -392,8 +416,8 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
                                    bool tail_bonus) {
   const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
   const int64_t tasks = v.R_L * v.C;
-  if ((tasks + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
-  const unsigned grid = (unsigned)((tasks + 3) / 4);
+  if (tasks > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;   // the kernels index chunks with 32 bits
+  const unsigned grid = (unsigned)((tasks + kStatsWaves - 1) / kStatsWaves);
   const bool sparse = (b->flags & DSSD_FLAG_SPARSE_SUPPORT) != 0;
   if (b->flags & DSSD_FLAG_EARLY_EXIT) {
     const Schedule sched = early_exit_schedule(c, b, v);
@@ -404,7 +428,8 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
   {
     Timed t(c, DSSD_K_ROW_STATS, s);
     with_flags([&](auto BF, auto AL, auto SP) {
-      DSSD_LAUNCH((row_chunk_stats<FLAG(BF), FLAG(AL), FLAG(SP)>), grid, s, v);
+      DSSD_LAUNCH_WG((row_chunk_stats<FLAG(BF), FLAG(AL), FLAG(SP)>), grid, kStatsWaves * kWave,
+                     occupancy_cap_lds(c, kStatsWaves, c->stats_waves_per_cu, grid), s, v);
     }, bf16, al, sparse);
   }
   {
@@ -442,12 +467,18 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   const int32_t groups = (v.C + 3) / 4;
   if ((int64_t)groups * b->B > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
   const unsigned grid = (unsigned)(groups * b->B);
-  // Few chunk waves: one launch, the last wave of each session draws the token.  Many: two.
-  const bool fuse = (int64_t)b->B * v.C <= 4096;
+  // Few workgroups: one launch, the last workgroup of each session to finish its chunk masses
+  // draws the token.  Many: the arrival (a store that must be acknowledged, a barrier, an atomic
+  // that must return) holds every workgroup's wave slots a few microseconds longer with nothing
+  // in flight, which costs a streaming kernel more than the second launch does.
+#ifndef DSSD_RESID_FUSE_LIMIT
+#define DSSD_RESID_FUSE_LIMIT 1024
+#endif
+  const bool fuse = (int64_t)grid <= DSSD_RESID_FUSE_LIMIT;
   {
     Timed t(c, DSSD_K_RESID_MASS, s);
     with_flags([&](auto BF, auto AL, auto FP) {
-      DSSD_LAUNCH((resid_mass<FLAG(BF), FLAG(AL), FLAG(FP)>), grid, s, v, groups);
+      DSSD_LAUNCH_WG((resid_mass<FLAG(BF), FLAG(AL), FLAG(FP)>), grid, 256, occupancy_cap_lds(c, 4, c->resid_waves_per_cu, grid), s, v, groups);
     }, bf16, al, fuse);
   }
   if (!fuse) {
@@ -590,6 +621,13 @@ extern "C" dssd_status dssd_set_early_exit_schedule(dssd_ctx* c, const int32_t* 
     if (begin[r] <= begin[r - 1]) return DSSD_EINVAL;
   for (int r = 0; r < n; ++r) c->ee_begin[r] = begin[r];
   c->ee_rounds = n;
+  return DSSD_OK;
+}
+
+extern "C" dssd_status dssd_set_stream_occupancy(dssd_ctx* c, int32_t stats_waves_per_cu, int32_t resid_waves_per_cu) {
+  if (!c || stats_waves_per_cu < 0 || resid_waves_per_cu < 0) return DSSD_EINVAL;
+  c->stats_waves_per_cu = stats_waves_per_cu;
+  c->resid_waves_per_cu = resid_waves_per_cu;
   return DSSD_OK;
 }
 

@@ -21,8 +21,8 @@ __device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cas
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
 __device__ __forceinline__ float neg_inf() { return as_float(0xFF800000u); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-// largest float below a positive finite x
-__device__ __forceinline__ float next_below(float x) { return as_float(as_u32(x) - 1u); }
+// largest float below a positive finite x; 0 for x <= 0
+__device__ __forceinline__ float next_below(float x) { return x > 0.f ? as_float(as_u32(x) - 1u) : 0.f; }
 
 // ------------------------------------------------------------------ Philox4x32-10
 // Counter-based generator of Salmon, Moraes, Dror and Shaw (SC'11): ten rounds, each
@@ -81,13 +81,22 @@ __device__ __forceinline__ float wave_sum(float x) {
   x += dpp<0x140>(x);
   return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
 }
-// Inclusive prefix sum over the 64 lanes, in lane order.
-__device__ __forceinline__ float wave_scan(float x, int lane) {
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const float up = __shfl_up(x, d, kWave);
-    if (lane >= d) x += up;
-  }
+// Inclusive prefix sum over the 64 lanes, in lane order, on the DPP path (no LDS traffic): four
+// shifted adds inside each row of 16 lanes (a lane whose source falls outside its row adds 0),
+// then lane 15 of rows 0 and 2 is broadcast into rows 1 and 3, then lane 31 into the upper half.
+// Each lane sums its own tree, so with rounding the result need not be monotone across lanes:
+// callers that search it for a threshold must also ask for a positive weight.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_or_zero(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_scan(float x, int /*lane*/) {
+  x += dpp_or_zero<0x111, 0xF>(x);   // row_shr:1
+  x += dpp_or_zero<0x112, 0xF>(x);   // row_shr:2
+  x += dpp_or_zero<0x114, 0xF>(x);   // row_shr:4
+  x += dpp_or_zero<0x118, 0xF>(x);   // row_shr:8
+  x += dpp_or_zero<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+  x += dpp_or_zero<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3
   return x;
 }
 

@@ -30,8 +30,8 @@ __global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32
   const int32_t t = j * 4 + wave;
   if (t < ntask) {
     const int32_t i = t / a.C, c = t - i * a.C;
-    const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
-    const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, lrow0 + i), c, a.V, c1, lane);
+    auto c1_of = [&]() { return (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e; };
+    const float2 st = chunk_stats_of<BF16, ALIGNED>(logits_row<BF16>(a, lrow0 + i), c, a.V, c1_of, lane);
     if (lane == 0) {
       publish2(a.chunk_stats + (lrow0 + i) * a.C + c, st);
       stores_done();   // acknowledged before the barrier that precedes the arrival

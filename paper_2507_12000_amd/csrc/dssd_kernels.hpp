@@ -26,6 +26,7 @@ struct __attribute__((aligned(16))) Job {
 struct BatchView {
   int32_t B, V, gamma, C;            // C = chunks per row
   int32_t xcds;                      // XCDs of the device (round-robin targets of consecutive workgroups)
+  int32_t xcd_shift;                 // log2(xcds) when that is a power of two, else -1
   int64_t R_L, R_Q;
   const int32_t* offsets;            // may be null
   const void* logits;
@@ -55,12 +56,22 @@ struct BatchView {
   float* support_z;                  // [R_L, kMaxSupport]
 };
 
+// xcd_contiguous for grids below 2^31 workgroups, without a division when the XCD count is a
+// power of two.
+__device__ __forceinline__ uint32_t xcd_contiguous32(uint32_t block, uint32_t blocks, const BatchView& a) {
+  if (a.xcd_shift >= 0) {
+    const uint32_t per = blocks >> a.xcd_shift;
+    return block < (per << a.xcd_shift) ? (block & ((1u << a.xcd_shift) - 1u)) * per + (block >> a.xcd_shift) : block;
+  }
+  return (uint32_t)xcd_contiguous(block, blocks, (uint32_t)a.xcds);
+}
+
 __device__ __forceinline__ int64_t session_first_draft(const BatchView& a, int32_t b) {
   return a.offsets ? (int64_t)a.offsets[b] : (int64_t)b * a.gamma;
 }
 // Session that owns logits row `row`: the largest b with first_draft(b) + b <= row.
 __device__ __forceinline__ int32_t session_of_row(const BatchView& a, int64_t row) {
-  if (!a.offsets) return (int32_t)(row / (a.gamma + 1));
+  if (!a.offsets) return (int32_t)((uint32_t)row / (uint32_t)(a.gamma + 1));   // rows < 2^31
   int32_t lo = 0, hi = a.B - 1;
   while (lo < hi) {
     const int32_t mid = (lo + hi + 1) >> 1;
@@ -88,14 +99,17 @@ struct SupportRow {
 // SUPPORT: the wave also appends the chunk's finite entries to the row's support list (rows
 // are expected to be almost entirely -inf, e.g. after top-k filtering, so nearly every chunk
 // skips this at the cost of one wave-uniform branch).
-template <bool BF16, bool ALIGNED, bool SUPPORT = false>
-__device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int32_t V, float c1, int lane,
+// c1_of() yields log2(e)/T of the row; it is called after the chunk's loads have been issued, so
+// whatever it costs (a session lookup, a dependent load) runs under their latency.
+template <bool BF16, bool ALIGNED, bool SUPPORT = false, class C1Fn>
+__device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int32_t V, C1Fn c1_of, int lane,
                                                  SupportRow sup = SupportRow{}) {
   constexpr int E = Elems<BF16>::per_vec;
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
   float z[kUnroll][E];
 #pragma unroll
   for (int k = 0; k < kUnroll; ++k) load_logits<BF16, ALIGNED>(src, v0 + k * kWave, V, z[k]);
+  const float c1 = c1_of();
 
   float mx = neg_inf();
 #pragma unroll
@@ -133,19 +147,29 @@ __device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int
   return make_float2(m2, s);
 }
 
+// Workgroups of kStatsWaves waves, one chunk each.  How many of them share a compute unit is
+// capped by the host at launch (see occupancy_cap_lds): the workgroup size itself made no
+// difference once the waves in flight per unit were held equal (4, 8 and 16 waves measured).
+constexpr int kStatsWaves = 4;
 template <bool BF16, bool ALIGNED, bool SUPPORT>
-__global__ __launch_bounds__(256) void row_chunk_stats(const BatchView a) {
+__global__ __launch_bounds__(kStatsWaves * kWave) void row_chunk_stats(const BatchView a) {
+  // Everything before the loads is wave-uniform 32-bit arithmetic (the host refuses batches with
+  // 2^31 chunks or more), so a wave has its loads in flight a few dozen scalar instructions
+  // after it starts.
   const int lane = threadIdx.x & 63;
-  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x, a.xcds) * 4 + (threadIdx.x >> 6);
-  if (task >= a.R_L * a.C) return;
-  const int64_t row = task / a.C;
-  const int32_t c = (int32_t)(task - row * a.C);
-  float c1 = kLog2e;
-  if (a.inv_temp) c1 *= a.inv_temp[session_of_row(a, row)];
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t C = (uint32_t)a.C;
+  const uint32_t tasks = (uint32_t)a.R_L * C;
+  const uint32_t task = xcd_contiguous32(blockIdx.x, gridDim.x, a) * kStatsWaves + wave;
+  if (task >= tasks) return;
+  const uint32_t row = task / C;
+  const int32_t c = (int32_t)(task - row * C);
   SupportRow sup{};
   if constexpr (SUPPORT)
-    sup = SupportRow{a.support_count + row, a.support_idx + row * kMaxSupport, a.support_z + row * kMaxSupport};
-  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, row), c, a.V, c1, lane, sup);
+    sup = SupportRow{a.support_count + row, a.support_idx + (int64_t)row * kMaxSupport,
+                     a.support_z + (int64_t)row * kMaxSupport};
+  auto c1_of = [&]() { return a.inv_temp ? kLog2e * a.inv_temp[session_of_row(a, row)] : kLog2e; };
+  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, row), c, a.V, c1_of, lane, sup);
   if (lane == 0) a.chunk_stats[task] = st;
 }
 
@@ -396,9 +420,7 @@ __device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, 
 
 // Residual resample (Algorithm 2 "Resample"): mass of max(0, P - Q) per chunk of the rejected
 // row, one wave per chunk.  Sessions that were not rejected exit at once.  FUSE_PICK: the last
-// wave of a session to finish also draws the token, which saves the second launch -- worth it
-// for small batches only (measured: the per-wave arrival costs more than a launch once there
-// are more than a few thousand chunk waves).
+// workgroup of a session to finish also draws the token, which saves the second launch.
 template <bool BF16, bool ALIGNED>
 __device__ __forceinline__ float resid_chunk_mass(const BatchView& a, int32_t b, const Job& job, int32_t c,
                                                   int lane) {
@@ -408,53 +430,92 @@ __device__ __forceinline__ float resid_chunk_mass(const BatchView& a, int32_t b,
   const float invZ = 1.f / st.y;
   const char* lp = logits_row<BF16>(a, job.lrow);
   const float* qp = a.draft_probs + (job.lrow - b) * (int64_t)a.V;   // draft row = logits row - session
-  const int64_t v0 = (int64_t)c * kChunkVecs + lane;
-  // Two half-chunks of 4 groups each (12 loads in flight per lane): measured faster than all 8
-  // groups at once, which costs occupancy (three input streams here, not one).
   float acc = 0.f;
+  if constexpr (BF16 && ALIGNED) {
+    // Lane l takes elements [4l, 4l+4) of every 256-entry half-block: an 8-byte load of logits and
+    // a 16-byte load of Q, so that every wave instruction reads one contiguous stretch of its row
+    // (with 8 elements per lane the Q loads would touch only half of each cache line they visit:
+    // measured 6 % slower).  All 32 loads of the chunk are in flight at once.
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    constexpr int kHalves = chunk_elems<true>() / 256;
+    const int64_t e_chunk = (int64_t)c * chunk_elems<true>() + lane * 4;
+    u32x2 z[kHalves];
+    f32x4 q[kHalves];
 #pragma unroll
-  for (int k0 = 0; k0 < kUnroll; k0 += 4) {
-    float z[4][E], q[4][E];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
-      load_probs<E, ALIGNED>(qp, (v0 + (k0 + k) * kWave) * E, a.V, q[k]);
+    for (int h = 0; h < kHalves; ++h) {
+      const int64_t e0 = e_chunk + h * 256;
+      const bool inside = e0 < a.V;                     // V is a multiple of 8: inside means entirely inside
+      const int64_t ec = inside ? e0 : (int64_t)a.V - 4;
+      z[h] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(lp + ec * 2));
+      q[h] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(qp + ec));
+      if (!inside) {
+        z[h] = (u32x2){0xFF80FF80u, 0xFF80FF80u};
+        q[h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
+    for (int h = 0; h < kHalves; ++h) {
+      const float z0 = as_float(z[h][0] << 16), z1 = as_float(z[h][0] & 0xFFFF0000u);
+      const float z2 = as_float(z[h][1] << 16), z3 = as_float(z[h][1] & 0xFFFF0000u);
+      acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z0, c1, -st.x)), invZ, -q[h][0]));
+      acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z1, c1, -st.x)), invZ, -q[h][1]));
+      acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z2, c1, -st.x)), invZ, -q[h][2]));
+      acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z3, c1, -st.x)), invZ, -q[h][3]));
+    }
+  } else {
+    // fp32 logits are 4 per 16-byte group, like Q: already one contiguous stretch per instruction.
+    // Two half-chunks of 4 groups each (unaligned rows take the scalar loads of load_logits).
+    const int64_t v0 = (int64_t)c * kChunkVecs + lane;
 #pragma unroll
-      for (int e = 0; e < E; ++e)
-        acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z[k][e], c1, -st.x)), invZ, -q[k][e]));
+    for (int k0 = 0; k0 < kUnroll; k0 += 4) {
+      float z[4][E], q[4][E];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
+        load_probs<E, ALIGNED>(qp, (v0 + (k0 + k) * kWave) * E, a.V, q[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z[k][e], c1, -st.x)), invZ, -q[k][e]));
+    }
   }
   return wave_sum(acc);
 }
 
 template <bool BF16, bool ALIGNED, bool FUSE_PICK>
 __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t groups) {
+  __shared__ int32_t sh_last;
   const int lane = threadIdx.x & 63;
   const int64_t blk = blockIdx.x;   // plain order: measured faster here than the XCD-contiguous map
   const int32_t b = (int32_t)(blk / groups);
   const int32_t c = (int32_t)(blk - (int64_t)b * groups) * 4 + (threadIdx.x >> 6);
-  if (c >= a.C) return;
   const Job job = a.resid_job[b];
-  if (job.lrow < 0) return;
-  const float acc = resid_chunk_mass<BF16, ALIGNED>(a, b, job, c, lane);
-  if constexpr (!FUSE_PICK) {
-    if (lane == 0) a.resid_mass[(int64_t)b * a.C + c] = acc;
-    return;
+  if (job.lrow < 0) return;          // the whole workgroup: the job belongs to the session
+  if (c < a.C) {
+    const float acc = resid_chunk_mass<BF16, ALIGNED>(a, b, job, c, lane);
+    if constexpr (!FUSE_PICK) {
+      if (lane == 0) a.resid_mass[(int64_t)b * a.C + c] = acc;
+    } else if (lane == 0) {
+      publish(a.resid_mass + (int64_t)b * a.C + c, acc);
+      stores_done();   // acknowledged before the barrier that precedes the arrival
+    }
   }
-  // The wave that completes the session's C chunk masses draws the token.  The masses are
-  // published with device-coherent stores and read back with device-coherent loads, so the
-  // arrival counter needs no cache-wide fence.  The counter is left at zero for the next call.
-  int32_t arrived = 0;
-  if (lane == 0) {
-    publish(a.resid_mass + (int64_t)b * a.C + c, acc);
-    arrived = arrive(a.arrive_resid + b);
+  if constexpr (!FUSE_PICK) return;
+  // The workgroup that completes the session's chunk masses draws the token (one arrival per
+  // workgroup, nobody waits).  The masses are published with device-coherent stores and read
+  // back with device-coherent loads, so the arrival counter needs no cache-wide fence.  The
+  // counter is left at zero for the next call.
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const bool last =
+        __hip_atomic_fetch_add(a.arrive_resid + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == groups - 1;
+    if (last) __hip_atomic_store(a.arrive_resid + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sh_last = last;
   }
-  arrived = __builtin_amdgcn_readfirstlane(arrived);
-  if (arrived != a.C - 1) return;
-  if (lane == 0) __hip_atomic_store(a.arrive_resid + b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  pick_for_session<BF16, ALIGNED, true>(a, b, job, lane);
+  __syncthreads();
+  if (sh_last && threadIdx.x < kWave) pick_for_session<BF16, ALIGNED, true>(a, b, job, lane);
 }
 
 // Inverse-CDF draw inside one chunk: target in [0, chunk mass) -> vocabulary index.
@@ -462,7 +523,8 @@ __global__ __launch_bounds__(256) void resid_mass(const BatchView a, int32_t gro
 // the local target is clamped into [0, local total) so that a token is always found and a
 // zero-weight token never is.
 // `wf.group(g, w)` fills the W::E weights of group g of the row and returns their sum (summed in
-// element order); the same functor must have produced the chunk masses.
+// element order).  The chunk masses the target came from may have been summed in another order:
+// the clamps absorb the difference.
 template <typename W>
 __device__ __forceinline__ int32_t pick_in_chunk(const W& wf, int32_t c, float target, int lane) {
   constexpr int E = W::E;
@@ -487,7 +549,7 @@ __device__ __forceinline__ int32_t pick_in_chunk(const W& wf, int32_t c, float t
 #pragma unroll
   for (int k = 0; k < kUnroll; ++k) {
     const float upto = run + S[k];
-    if (!found && upto > t) { found = true; ksel = k; before = run; }
+    if (!found && upto > t && S[k] > 0.f) { found = true; ksel = k; before = run; }
     run = upto;
   }
   float my_sum = 0.f, my_scan = 0.f, Ssel = 0.f;
@@ -495,9 +557,12 @@ __device__ __forceinline__ int32_t pick_in_chunk(const W& wf, int32_t c, float t
   for (int k = 0; k < kUnroll; ++k)
     if (k == ksel) { my_sum = lsum[k]; my_scan = scan[k]; Ssel = S[k]; }
   // lane
+  // (a lane of zero weight can sit one rounding above its predecessor in the scan: never taken)
   float t2 = fminf(fmaxf(t - before, 0.f), next_below(Ssel));
-  const uint64_t over = __ballot(my_scan > t2);
-  const int lsel = over ? __ffsll((long long)over) - 1 : 63;
+  const uint64_t weighty = __ballot(my_sum > 0.f);
+  const uint64_t over = __ballot(my_scan > t2 && my_sum > 0.f);
+  if (!weighty) return -1;
+  const int lsel = over ? __ffsll((long long)over) - 1 : 63 - __clzll((long long)weighty);
   const float excl = lsel > 0 ? lane_value(my_scan, lsel - 1) : 0.f;
   const float sum_sel = lane_value(my_sum, lsel);
   const float t3 = fminf(fmaxf(t2 - excl, 0.f), next_below(sum_sel));
@@ -536,20 +601,31 @@ __device__ __forceinline__ int32_t pick_chunk(MassFn mass, int32_t C, float r, i
   if (!(run > 0.f) || !(run < 3.0e38f)) return -1;
   const float t = fminf(__fmul_rn(r, run), next_below(run));
   run = 0.f;
+  int32_t last_weighty = -1;
+  float before_last = 0.f;
   for (int32_t base = 0; base < C; base += kWave) {
     const int32_t c = base + lane;
-    const float sc = wave_scan(c < C ? mass(c) : 0.f, lane);
-    const uint64_t over = __ballot((run + sc) > t);
+    const float m = c < C ? mass(c) : 0.f;
+    const float sc = wave_scan(m, lane);
+    // a chunk of zero mass can sit one rounding above its predecessor in the scan: never taken
+    const uint64_t weighty = __ballot(m > 0.f);
+    const uint64_t over = __ballot((run + sc) > t && m > 0.f);
     if (over) {
       const int lsel = __ffsll((long long)over) - 1;
       const float before = lsel > 0 ? run + lane_value(sc, lsel - 1) : run;
       *target_in_chunk = t - before;
       return base + lsel;
     }
+    if (weighty) {
+      const int l = 63 - __clzll((long long)weighty);
+      last_weighty = base + l;
+      before_last = l > 0 ? run + lane_value(sc, l - 1) : run;
+    }
     run = run + lane_value(sc, 63);
   }
-  *target_in_chunk = 0.f;   // not reachable: the last prefix equals the total, which exceeds t
-  return C - 1;
+  // rounding left no prefix above t: the last chunk that has mass (pick_in_chunk clamps the target)
+  *target_in_chunk = t - before_last;
+  return last_weighty;
 }
 
 // One wave per session.  RESID: rejected sessions, row n, weights max(0, P - Q), r = word 1 of
@@ -626,8 +702,11 @@ __device__ __forceinline__ int32_t draw_from_ranked(float w_ranked, int32_t idx_
   const float total = lane_value(scan, 63);
   if (!(total > 0.f) || !(total < 3.0e38f)) return -1;
   const float t = fminf(__fmul_rn(r, total), next_below(total));
-  const uint64_t over = __ballot(scan > t);
-  const int sel = over ? __ffsll((long long)over) - 1 : 63;
+  // an entry of zero weight (padding included) can sit one rounding above its predecessor in
+  // the scan: never taken
+  const uint64_t weighty = __ballot(w_ranked > 0.f);
+  const uint64_t over = __ballot(scan > t && w_ranked > 0.f);
+  const int sel = over ? __ffsll((long long)over) - 1 : 63 - __clzll((long long)weighty);
   return __shfl(idx_ranked, sel, kWave);
 }
 

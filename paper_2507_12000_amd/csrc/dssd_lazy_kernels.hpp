@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, i
   SupportRow sup{};
   if constexpr (SUPPORT)
     sup = SupportRow{a.support_count + lrow, a.support_idx + lrow * kMaxSupport, a.support_z + lrow * kMaxSupport};
-  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, lrow), c, a.V, c1, lane, sup);
+  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, lrow), c, a.V, [=]() { return c1; }, lane, sup);
   if (lane == 0) a.chunk_stats[lrow * a.C + c] = st;
 }
 
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, c
     if constexpr (SUPPORT)
       sup = SupportRow{a.support_count + t.lrow, a.support_idx + t.lrow * kMaxSupport,
                        a.support_z + t.lrow * kMaxSupport};
-    const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, t.lrow), c, a.V, t.c1, lane, sup);
+    const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, t.lrow), c, a.V, [=]() { return t.c1; }, lane, sup);
     if (lane == 0) a.chunk_stats[t.lrow * a.C + c] = st;
   }
 }
