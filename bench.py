@@ -22,20 +22,24 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM bytes per launch of row_chunk_stats from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy of known size; profiles/row_chunk_stats_cfg4_pmc.txt).
-# Valid only for the kernel sources they were taken with: reported as null once those change.
+# Taken in profiler runs of their own, not in the run that prints them, and valid only for the
+# sources they were taken with: reported as null once any file the kernel and its launch are made
+# of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
         "sources_sha256": "6eac15ab4213c4bb38360e712234c6b7b52efc319e3912c81d5cb5596ab3358d",
         "bytes_per_launch": int((2426304.1 * 2.0 + 4776.7 * 1.0) * 1024),
+        "source": "profiles/row_chunk_stats_cfg4_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }
+KERNEL_SOURCES = ("dssd_device.hpp", "dssd_kernels.hpp", "dssd.hip")   # what row_chunk_stats and its launch are made of
 
 
 def kernel_sources_digest():
     import hashlib
     d = os.path.join(ROOT, "paper_2507_12000_amd", "csrc")
     h = hashlib.sha256()
-    for name in ("dssd_device.hpp", "dssd_kernels.hpp"):   # the files row_chunk_stats is made of
+    for name in KERNEL_SOURCES:
         h.update(name.encode())
         with open(os.path.join(d, name), "rb") as f:
             h.update(f.read())
@@ -256,6 +260,101 @@ def time_split_path(ctx, D, torch, inputs, outs, args):
             "downlink_bytes_per_rejected_session": V * 2, "uplink_bytes_per_position": 8}
 
 
+def step_event_stats(torch, run_step, n, first_step):
+    """n steps, each bracketed by a pair of HIP events on the launch stream (torch's current
+    stream, which the library launches on): median / min / max of one step.  A region of its own:
+    the brackets cost queue time, so `value` never comes from here."""
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for k, (a, b) in enumerate(pairs):
+        a.record()
+        run_step(first_step + k)
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in pairs)
+    return {"median_ms": ms[len(ms) // 2], "min_ms": ms[0], "max_ms": ms[-1], "steps": n}
+
+
+PROBE_LOADS = (1, 2, 4, 8)
+PROBE_CAPS = (0, 8, 12, 16, 24)
+
+
+def read_ceiling(ctx, D, torch, buf, nbytes, launches=12):
+    """Best rate of the pure-read probe over loads per lane and waves resident per compute unit:
+    the read ceiling of this chip for the statistics kernel's kind of access."""
+    best, table = None, {}
+    for loads in PROBE_LOADS:
+        for cap in PROBE_CAPS:
+            for _ in range(2):
+                D.dssd_probe_read(ctx.handle, buf, nbytes, loads, cap, ctx.stream())
+            torch.cuda.synchronize()
+            D.dssd_profile_reset(ctx.handle)
+            D.dssd_profile_enable(ctx.handle, 1 << D.K_READ_PROBE)
+            for _ in range(launches):
+                D.dssd_probe_read(ctx.handle, buf, nbytes, loads, cap, ctx.stream())
+            torch.cuda.synchronize()
+            D.dssd_profile_enable(ctx.handle, False)
+            ms, n = D.dssd_profile_read(ctx.handle, D.K_READ_PROBE)
+            unit = 1024 * loads
+            rate = (nbytes // unit) * unit / (ms / n * 1e-3) / 1e9
+            table[f"loads{loads}_cap{cap}"] = round(rate, 1)
+            if best is None or rate > best[0]:
+                best = (rate, loads, cap)
+    return {"GBps": best[0], "loads_per_lane": best[1], "waves_per_cu": best[2], "all_GBps": table}
+
+
+def config_summary(D, torch, synth, idx, seed, steps, warmup):
+    """One benchmark workload, briefly: the three calls and the whole-step call (wall-clock mean,
+    and per-step events for the spread), the statistics kernel's rate, the whole step's rate."""
+    dev = "cuda:0"
+    w = synth.WORKLOADS[idx]
+    inputs = synth.generate(w, seed=seed, device=dev)
+    torch.cuda.synchronize()
+    ctx = D.Context(dev, max_rows=inputs["R_L"], max_V=w.V)
+    batch = D.make_batch(inputs, seed=seed, step=0)
+    outs, out = D.alloc_out(inputs, dev, debug=False)
+    res = {"workload": w.name, "logits_rows": inputs["R_L"], "draft_positions": inputs["R_Q"]}
+
+    def timed(run):
+        def one(step):
+            batch.step = step
+            run(batch, out)
+        for k in range(warmup):
+            one(k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            one(warmup + k)
+        torch.cuda.synchronize()
+        mean_ms = 1e3 * (time.perf_counter() - t0) / steps
+        return mean_ms, step_event_stats(torch, one, min(steps, 100), warmup + steps)
+
+    D.dssd_profile_reset(ctx.handle)
+    D.dssd_profile_enable(ctx.handle, 1 << D.K_ROW_STATS)
+    mean3, ev3 = timed(ctx.step)
+    D.dssd_profile_enable(ctx.handle, False)
+    k1_ms, k1_n = D.dssd_profile_read(ctx.handle, D.K_ROW_STATS)
+    meanf, evf = timed(ctx.step_fused)
+    rejected = outs["rejected"].cpu().numpy()
+    s_L = inputs["logits"].element_size()
+    C = -(-w.V // (4096 if s_L == 2 else 2048))
+    ab = algorithmic_bytes(inputs, rejected, 1.0 / C)
+    k1_us = 1e3 * k1_ms / max(k1_n, 1)
+    res.update({
+        "three_calls": {"ms_per_step": mean3, "positions_per_sec": inputs["R_Q"] / (mean3 * 1e-3), "events": ev3},
+        "whole_step_call": {"ms_per_step": meanf, "positions_per_sec": inputs["R_Q"] / (meanf * 1e-3), "events": evf},
+        "row_chunk_stats": {"avg_launch_us": k1_us, "GBps": ab["row_stats"] / (k1_us * 1e-6) / 1e9,
+                            "frac_of_hbm_peak": ab["row_stats"] / (k1_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+        "step_algorithmic_bytes": ab["total"],
+        "step_frac_of_hbm_peak": ab["total"] / (mean3 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "rejected_sessions": int(rejected.sum()),
+        "note": ("launch-latency-bound" if idx == 0 else "inputs fit the last-level cache" if idx == 1 else None),
+    })
+    ctx.close()
+    del inputs, batch, outs, out
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--fused", action="store_true",
@@ -286,6 +385,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="index into the five benchmark workloads")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="skip the brief runs of the other benchmark workloads after the headline")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip the figures beside the headline (whole-step call, early exit, two batches in "
                          "flight): what a profiler run of the headline kernels wants")
@@ -405,10 +506,16 @@ def main():
     if flags & D.FLAG_SPARSE_SUPPORT:   # the samplers touch a few dozen entries per session, not rows
         ab["total"] -= ab["residual"] + ab["bonus"]
         ab["residual"] = ab["bonus"] = 0
-    if args.early_exit:   # rows 0..n_b of every session are read, nothing after the first rejection
-        visited = int((outs["accepted_len"].cpu().numpy().astype("int64") + 1).sum())
+    if args.early_exit:   # the rows of the blocks that were visited: their statistics are not NaN
+        dbg_t, dbg_out = D.alloc_out(inputs, dev, debug=True)
+        batch.step = 0
+        step_fn(batch, dbg_out)
+        torch.cuda.synchronize()
+        visited = int((~torch.isnan(dbg_t["row_stats"][:, 1])).sum().item())
+        del dbg_t, dbg_out
         ab["total"] += visited * w.V * s_L - ab["row_stats"]
         ab["row_stats"] = visited * w.V * s_L
+        ab["rows_visited"] = visited
     ms_per_step = 1e3 * elapsed / args.steps
     # dominant kernel: the row statistics, or the single fused launch when the step ran as one
     dom = D.kernel_name(dom_id)
@@ -425,7 +532,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32", "accum_dtype": "f32", "logits_dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "entry": "dssd_step_fused" if args.fused else
                    "dssd_verify_batch+dssd_residual_sample+dssd_bonus_sample", "B": w.B, "V": w.V, "logits_dtype": w.dtype,
                    "input_copies_rotated": max(args.rotate, 1), "top_k": args.top_k, "sparse_support": bool(flags & D.FLAG_SPARSE_SUPPORT),
@@ -438,8 +545,8 @@ def main():
         "kernels_separate_region": kernels,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "algorithmic_bytes_per_launch": dom_bytes,
-                     "avg_launch_us": k1_us},
+                     "traffic": traffic, "traffic_source": pmc["source"] if traffic else None,
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": k1_us},
     }
     # The paper's communication model (Sec. 2.2, 3.1) fed with what this step measured: the share
     # of sessions with a rejection is its indicator a.  Link as in Table 1: T_NTT = 20 ms and 8 ms
@@ -453,23 +560,21 @@ def main():
         "mean_gamma": mean_gamma, "rejected_share": float(rejected.mean()),
         "dsd_comm_ms": 1e3 * (mean_gamma * LM.distribution_bits(w.V, 16) / link.rate_up + link.t_ntt),
         "dssd_comm_ms": 1e3 * LM.dssd_comm_time_from_flags(rejected.tolist(), w.V, 16, link)}
-    # read ceiling of this chip for the statistics kernel's access pattern, over the same buffer
+    # read ceiling of this chip for the statistics kernel's kind of access, over the same buffer:
+    # the best of a sweep of the pure-read probe
     lg = inputs["logits"]
     nbytes = lg.numel() * lg.element_size()
     if nbytes >= (256 << 20):
-        for _ in range(3):
-            D.dssd_probe_read(ctx.handle, lg.data_ptr(), nbytes, ctx.stream())
-        torch.cuda.synchronize()
-        D.dssd_profile_reset(ctx.handle)
-        D.dssd_profile_enable(ctx.handle, 1 << D.K_READ_PROBE)
-        for _ in range(20):
-            D.dssd_probe_read(ctx.handle, lg.data_ptr(), nbytes, ctx.stream())
-        torch.cuda.synchronize()
-        D.dssd_profile_enable(ctx.handle, False)
-        ms, n = D.dssd_profile_read(ctx.handle, D.K_READ_PROBE)
-        ceiling = (nbytes // 8192) * 8192 / (ms / n * 1e-3) / 1e9
-        result["roofline"]["measured_read_ceiling_GBps"] = ceiling
-        result["roofline"]["frac_of_measured_read_ceiling"] = achieved / ceiling
+        ceil = read_ceiling(ctx, D, torch, lg.data_ptr(), nbytes)
+        result["roofline"]["measured_read_ceiling_GBps"] = ceil["GBps"]
+        result["roofline"]["measured_read_ceiling_probe"] = {k: ceil[k] for k in ("loads_per_lane", "waves_per_cu")}
+        result["roofline"]["frac_of_measured_read_ceiling"] = achieved / ceil["GBps"]
+        result["roofline"]["probe_sweep_GBps"] = ceil["all_GBps"]
+    # spread of one step: per-step HIP events in a region of their own
+    def one_step(step):
+        batch.step = step
+        step_fn(batch, out)
+    result["step_events"] = step_event_stats(torch, one_step, min(args.steps, 100), args.warmup + 2 * args.steps)
     if not args.fused and not args.early_exit and not args.headline_only:
         # the same step through the single whole-step call (bit-identical outputs; it folds the
         # bonus draw into the accept launch, or runs one launch for small batches): a second
@@ -543,6 +648,23 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inputs, args.seed, budget_s=15.0)
     ctx.close()
+    plain = (not args.fused and not args.early_exit and not args.headline_only and not args.no_all_configs
+             and args.top_k == 0 and args.rotate <= 1)
+    if plain:
+        # the other benchmark workloads, briefly (the headline's inputs are released first)
+        head = {"workload": w.name, "three_calls": {"ms_per_step": ms_per_step, "events": result["step_events"]},
+                "whole_step_call": result.get("whole_step_call"),
+                "row_chunk_stats": {"avg_launch_us": k1_us, "GBps": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS},
+                "step_frac_of_hbm_peak": result["step_frac_of_hbm_peak"]}
+        del inputs, batch, batches, copies, outs, out, lg
+        torch.cuda.empty_cache()
+        result["all_configs"] = {}
+        for idx in range(len(synth.WORKLOADS)):
+            if idx == args.config:
+                result["all_configs"][f"cfg{idx}"] = head
+            else:
+                result["all_configs"][f"cfg{idx}"] = config_summary(D, torch, synth, idx, args.seed,
+                                                                    steps=200 if idx < 2 else 60, warmup=10)
     print(json.dumps(result))
 
 

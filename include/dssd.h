@@ -24,7 +24,11 @@
  *   - Host-checkable errors return a negative status before anything is launched.  Errors that
  *     only the device can see (token id outside [0,V), inconsistent offsets, a logits row whose
  *     softmax is not finite) set status[b] and give that session accepted_len = 0,
- *     rejected = 1, out_token = -1; the samplers skip it.
+ *     rejected = 1, out_token = -1; the samplers skip it.  A bad token or row counts where the
+ *     loop of Algorithm 2 looks ("while j <= gamma and Flag = 1"): at positions and rows up to
+ *     the first rejected draft (whose row feeds the redraw), and at the bonus row when every
+ *     draft is accepted.  What lies after the first rejection is never looked at, so a fault
+ *     there changes nothing, on any entry point and in any mode.
  */
 #ifndef DSSD_H
 #define DSSD_H
@@ -75,9 +79,8 @@ enum {
    * launches are expected to cost more than the unread rows save), and a session leaves as soon as a block holds its first rejection or
    * its bonus row.  accepted_len, rejected and out_token are bit-identical to the default path,
    * and so are row_stats, p_tok and q_tok for the rows and positions of the blocks that were
-   * visited; entries of later blocks are NaN, and a fault (bad token, non-finite row) there
-   * goes unnoticed.  Honoured by dssd_verify_batch and dssd_step_fused; combines with
-   * DSSD_FLAG_SPARSE_SUPPORT. */
+   * visited; entries of later blocks are NaN.  Honoured by dssd_verify_batch and
+   * dssd_step_fused; combines with DSSD_FLAG_SPARSE_SUPPORT. */
   DSSD_FLAG_EARLY_EXIT = 2
 };
 #define DSSD_MAX_SUPPORT 64

@@ -57,10 +57,14 @@ dssd_status dssd_profile_read(dssd_ctx *ctx, int kernel_id, double *total_ms, in
 dssd_status dssd_profile_reset(dssd_ctx *ctx);
 const char *dssd_kernel_name(int kernel_id);
 
-/* Measurement aid: read `bytes` (rounded down to 8 KiB) of device memory at `buf` (16-byte
- * aligned) with the access pattern of the row-statistics kernel and no arithmetic.  Its rate is
- * the read ceiling that kernel can be held against on the chip at hand. */
-dssd_status dssd_probe_read(dssd_ctx *ctx, const void *buf, size_t bytes, void *hip_stream);
+/* Measurement aid: read `bytes` (rounded down to whole waves' shares) of device memory at `buf`
+ * (16-byte aligned) the way the row-statistics kernel reads, with no arithmetic: one wave per
+ * loads_per_lane KiB (1, 2, 4 or 8 non-temporal 128-bit loads per lane, all in flight), at most
+ * waves_per_cu waves resident per compute unit (0 = no cap; rounded as in
+ * dssd_set_stream_occupancy).  The best rate over these settings is the read ceiling that kernel
+ * can be held against on the chip at hand. */
+dssd_status dssd_probe_read(dssd_ctx *ctx, const void *buf, size_t bytes, int32_t loads_per_lane,
+                            int32_t waves_per_cu, void *hip_stream);
 
 /* ---- checking aids ---- */
 

@@ -231,14 +231,10 @@ void dssd_oracle_verify_session(const void* logits, int dtype, const float* draf
   res->resid_mass = 0.0; res->cdf_margin = 0.0;
   res->accept_margin = std::numeric_limits<double>::infinity();
 
-  for (int32_t i = 0; i < gamma; ++i)
-    if (tokens[i] < 0 || tokens[i] >= V) res->status |= 1;
-  if (res->status & 1) {  // malformed input: report, emit nothing
-    res->n = 0; res->rejected = 1;
-    return;
-  }
-
-  // Step 1 for every row, then the per-position scalars of step 2.
+  // Step 1 for every row, then the per-position scalars of step 2.  A draft token outside the
+  // vocabulary is malformed input: it counts where the loop of Algorithm 2 meets it (while
+  // Flag = 1), and then the session is reported and emits nothing; one that lies after the
+  // first rejection is never looked at, like everything else there.
   bool open = true;  // Flag = 1
   for (int32_t i = 0; i <= gamma; ++i) {
     double m, Z;
@@ -248,8 +244,9 @@ void dssd_oracle_verify_session(const void* logits, int dtype, const float* draf
     if (row_Z) row_Z[i] = Z;
     if (i == gamma) break;
     const float* Q = draft_probs + (size_t)i * (size_t)V;
-    const double p = P[tokens[i]];
-    const double q = (double)Q[tokens[i]];
+    const bool in_vocabulary = tokens[i] >= 0 && tokens[i] < V;
+    const double p = in_vocabulary ? P[tokens[i]] : 0.0;
+    const double q = in_vocabulary ? (double)Q[tokens[i]] : 0.0;
     uint32_t words[4];
     dssd_oracle_random_block(seed, step, session, (uint32_t)i, words);
     const double r = dssd_oracle_u01(words[0]);
@@ -262,6 +259,13 @@ void dssd_oracle_verify_session(const void* logits, int dtype, const float* draf
       beta[i] = b;
     }
     if (!open) continue;
+    if (!in_vocabulary) {  // malformed input met by the loop: report, emit nothing
+      open = false;
+      res->status |= 1;
+      res->n = 0; res->rejected = 1; res->token = -1;
+      res->accept_margin = std::numeric_limits<double>::infinity();
+      continue;
+    }
     // Step 2, and how close r came to its boundary.
     const double margin = dssd_oracle_accept_margin(r, p, q);
     if (margin < res->accept_margin) res->accept_margin = margin;
@@ -392,9 +396,6 @@ void dssd_oracle_edge_session(const void* logits, int dtype, const float* q_scal
   res->n = gamma; res->rejected = 0; res->token = -1; res->status = 0;
   res->resid_mass = 0.0; res->cdf_margin = 0.0;
   res->accept_margin = std::numeric_limits<double>::infinity();
-  for (int32_t i = 0; i < gamma; ++i)
-    if (tokens[i] < 0 || tokens[i] >= V) res->status |= 1;
-  if (res->status & 1) { res->n = 0; res->rejected = 1; return; }
   for (int32_t i = 0; i <= gamma; ++i) {
     double m, Z;
     dssd_oracle_softmax_row((const char*)logits + (size_t)i * (size_t)V * elem, dtype, V,
@@ -403,6 +404,11 @@ void dssd_oracle_edge_session(const void* logits, int dtype, const float* q_scal
     dssd_oracle_random_block(seed, step, session, (uint32_t)i, words);
     if (i == gamma) {   // all accepted: bonus token, word 2 of the position-gamma block
       res->token = dssd_oracle_inverse_cdf(P.data(), V, dssd_oracle_u01(words[2]), &res->cdf_margin);
+      return;
+    }
+    if (tokens[i] < 0 || tokens[i] >= V) {  // malformed input met by the loop: report, emit nothing
+      res->status |= 1; res->n = 0; res->rejected = 1;
+      res->accept_margin = std::numeric_limits<double>::infinity();
       return;
     }
     const double p = P[tokens[i]], q = (double)q_scalars[i], r = dssd_oracle_u01(words[0]);

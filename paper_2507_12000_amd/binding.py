@@ -112,7 +112,7 @@ def load():
     L.dssd_export_p_rows.restype = C.c_int
     L.dssd_residual_sample_from_p.argtypes = [P, C.POINTER(dssd_device_batch), P]
     L.dssd_residual_sample_from_p.restype = C.c_int
-    L.dssd_probe_read.argtypes = [P, P, C.c_size_t, P]
+    L.dssd_probe_read.argtypes = [P, P, C.c_size_t, C.c_int32, C.c_int32, P]
     L.dssd_probe_read.restype = C.c_int
     L.dssd_status_str.argtypes = [C.c_int]
     L.dssd_status_str.restype = C.c_char_p
@@ -225,8 +225,9 @@ def dssd_residual_sample_from_p(ctx, device_batch, stream=0, check=True):
     return rc
 
 
-def dssd_probe_read(ctx, ptr, nbytes, stream=0):
-    rc = load().dssd_probe_read(ctx, C.c_void_p(ptr), int(nbytes), C.c_void_p(stream or 0))
+def dssd_probe_read(ctx, ptr, nbytes, loads_per_lane=8, waves_per_cu=0, stream=0):
+    rc = load().dssd_probe_read(ctx, C.c_void_p(ptr), int(nbytes), int(loads_per_lane), int(waves_per_cu),
+                                C.c_void_p(stream or 0))
     if rc != DSSD_OK:
         raise DssdError(rc, "dssd_probe_read")
     return rc

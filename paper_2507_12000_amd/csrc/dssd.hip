@@ -64,7 +64,7 @@ struct dssd_ctx {
   // (measured: read throughput peaks near 16 waves of 8 KiB and falls off by several percent
   // towards full occupancy).  The caps below are waves per compute unit, enforced by asking for
   // LDS the kernels never touch; 0 = whatever the registers allow.
-  int32_t stats_waves_per_cu = 12;
+  int32_t stats_waves_per_cu = 16;
   int32_t resid_waves_per_cu = 8;
   int64_t max_rows = 0;
   int32_t max_V = 0;
@@ -701,17 +701,27 @@ extern "C" dssd_status dssd_residual_sample_from_p(dssd_ctx* c, const dssd_devic
   return launch_status(c);
 }
 
-extern "C" dssd_status dssd_probe_read(dssd_ctx* c, const void* buf, size_t bytes, void* hip_stream) {
-  if (!c || !buf) return DSSD_EINVAL;
+extern "C" dssd_status dssd_probe_read(dssd_ctx* c, const void* buf, size_t bytes, int32_t loads_per_lane,
+                                       int32_t waves_per_cu, void* hip_stream) {
+  if (!c || !buf || waves_per_cu < 0) return DSSD_EINVAL;
+  if (loads_per_lane != 1 && loads_per_lane != 2 && loads_per_lane != 4 && loads_per_lane != 8) return DSSD_EINVAL;
   if (reinterpret_cast<uintptr_t>(buf) & 15) return DSSD_EALIGN;
-  const int64_t chunks = (int64_t)(bytes / (kChunkVecs * 16));
-  if (chunks == 0) return DSSD_OK;
-  if ((chunks + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
+  const int64_t units = (int64_t)(bytes / ((size_t)kWave * 16 * loads_per_lane));
+  if (units == 0) return DSSD_OK;
+  if ((units + 3) / 4 > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int64_t grid = (units + 3) / 4;
+  const unsigned lds = occupancy_cap_lds(c, 4, waves_per_cu, grid);
+  const u32x4* src = static_cast<const u32x4*>(buf);
+  uint32_t* sink = reinterpret_cast<uint32_t*>(c->resid_mass);
   {
     Timed t(c, DSSD_K_READ_PROBE, s);
-    hipLaunchKernelGGL(read_probe, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, s,
-                       static_cast<const u32x4*>(buf), chunks, reinterpret_cast<uint32_t*>(c->resid_mass), c->xcds);
+    switch (loads_per_lane) {
+      case 1: DSSD_LAUNCH_WG(read_probe<1>, grid, 256, lds, s, src, units, sink, c->xcds); break;
+      case 2: DSSD_LAUNCH_WG(read_probe<2>, grid, 256, lds, s, src, units, sink, c->xcds); break;
+      case 4: DSSD_LAUNCH_WG(read_probe<4>, grid, 256, lds, s, src, units, sink, c->xcds); break;
+      default: DSSD_LAUNCH_WG(read_probe<8>, grid, 256, lds, s, src, units, sink, c->xcds); break;
+    }
   }
   return launch_status(c);
 }

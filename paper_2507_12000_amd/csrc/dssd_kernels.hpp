@@ -178,20 +178,22 @@ __global__ __launch_bounds__(256) void zero_i32(int32_t* p, int64_t n) {
   if (i < n) p[i] = 0;
 }
 
-// Measurement aid: the access pattern of row_chunk_stats (one wave per 8 KiB, eight non-temporal
-// 128-bit loads per lane, XCD-contiguous block order) with no arithmetic but an OR.  What this
-// reaches is the read bandwidth the statistics kernel can be held against on a given chip.
-__global__ __launch_bounds__(256) void read_probe(const u32x4* src, int64_t chunks, uint32_t* sink, int32_t xcds) {
+// Measurement aid: a pure read of the statistics kernel's kind (one wave per LOADS KiB, LOADS
+// non-temporal 128-bit loads per lane all in flight, XCD-contiguous block order) with no
+// arithmetic but an OR.  Swept over LOADS and over the waves resident per compute unit, its best
+// rate is the read ceiling the statistics kernel can be held against on a given chip.
+template <int LOADS>
+__global__ __launch_bounds__(256) void read_probe(const u32x4* src, int64_t units, uint32_t* sink, int32_t xcds) {
   const int lane = threadIdx.x & 63;
-  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x, xcds) * 4 + (threadIdx.x >> 6);
-  if (task >= chunks) return;
-  const u32x4* p = src + task * kChunkVecs + lane;
+  const int64_t unit = xcd_contiguous(blockIdx.x, gridDim.x, xcds) * 4 + (threadIdx.x >> 6);
+  if (unit >= units) return;
+  const u32x4* p = src + unit * (kWave * LOADS) + lane;
   uint32_t acc = 0;
-  u32x4 v[kUnroll];
+  u32x4 v[LOADS];
 #pragma unroll
-  for (int k = 0; k < kUnroll; ++k) v[k] = __builtin_nontemporal_load(p + k * kWave);
+  for (int k = 0; k < LOADS; ++k) v[k] = __builtin_nontemporal_load(p + k * kWave);
 #pragma unroll
-  for (int k = 0; k < kUnroll; ++k) acc |= v[k][0] | v[k][1] | v[k][2] | v[k][3];
+  for (int k = 0; k < LOADS; ++k) acc |= v[k][0] | v[k][1] | v[k][2] | v[k][3];
   if (acc == 0x5EEDF00Du) sink[0] = acc;   // keeps the loads alive; practically never taken
 }
 
@@ -315,16 +317,23 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, i
             if (a.q_tok) a.q_tok[qrow] = q;
           }
         }
+        // Faults count where Algorithm 2's loop looks: positions and rows up to the first
+        // rejection (its row feeds the redraw), or all of them and the bonus row when every
+        // draft is accepted.  A fault stops the loop where it stands, like a rejection would.
+        const bool was_open = first_reject == g && !(bad & 9);
         const uint64_t rej_mask = __ballot(reject);
-        if (rej_mask && first_reject == g) {
-          const int idx = __ffsll((long long)rej_mask) - 1;
-          first_reject = base + idx;
-          sel_st = row_st[idx];
-        } else if (first_reject == g && base + nrows - 1 == g) {
-          sel_st = row_st[nrows - 1];        // all accepted: the bonus row
-        }
         const uint64_t b1 = __ballot(lane_bad & 1), b8 = __ballot(lane_bad & 8);
-        bad |= (b1 ? 1 : 0) | (b8 ? 8 : 0);
+        const int idx = rej_mask ? __ffsll((long long)rej_mask) - 1 : kWave;   // first rejection of this pass
+        const uint64_t upto = idx >= kWave - 1 ? ~0ull : (2ull << idx) - 1ull;  // lanes 0..idx
+        if (was_open) {
+          bad |= ((b1 & upto) ? 1 : 0) | ((b8 & upto) ? 8 : 0);
+          if (rej_mask) {
+            first_reject = base + idx;
+            sel_st = row_st[idx];
+          } else if (base + nrows - 1 == g) {
+            sel_st = row_st[nrows - 1];        // all accepted: the bonus row
+          }
+        }
       }
       __syncthreads();
     }

@@ -411,23 +411,65 @@ def test_graph_replays_draw_fresh_numbers_through_the_step_counter(ctx):
     assert D.dssd_verify_batch(ctx.handle, bad, out, ctx.stream(), check=False) == D.DSSD_EALIGN
 
 
-def test_non_finite_logits_are_flagged_not_followed(ctx):
-    """A NaN or +inf logit poisons its row's softmax: the session is reported (BAD_ROW) and
-    skipped by the samplers; its neighbours are untouched."""
-    w = synth.Workload("nonfinite", B=8, V=9000, gamma=3, dtype="f32", sigmas=(1.0,))
+def _first(mask):
+    idx = np.flatnonzero(mask)
+    assert idx.size, "the workload has no session of the kind the test needs"
+    return int(idx[0])
+
+
+def test_faults_count_where_the_loop_looks(ctx):
+    """A NaN or +inf logit poisons its row's softmax and a token id outside the vocabulary cannot be
+    looked up: the session is reported and skipped by the samplers -- if Algorithm 2's loop gets
+    there (rows and positions up to the first rejection; the bonus row when every draft is
+    accepted).  The same fault after the first rejection is never looked at, on any path: the
+    three calls, the whole-step call (streamed and single launch) and the early-exit rounds give
+    the clean result.  Neighbours are untouched."""
+    w = synth.Workload("faults", B=48, V=9000, gamma=3, dtype="f32", sigmas=(1.0,))
     inputs = synth.generate(w, seed=4, device=DEV)
-    clean = gpu_step(ctx, inputs, 2, 2)
-    bad = dict(inputs, logits=inputs["logits"].clone())
     g = w.gamma
-    bad["logits"][2 * (g + 1) + 1, 17] = float("nan")       # session 2, row 1
-    bad["logits"][5 * (g + 1) + g, 4000] = float("inf")     # session 5, bonus row
-    got = gpu_step(ctx, bad, 2, 2)
-    for b in (2, 5):
-        assert got["status"][b] & D.SESSION_BAD_ROW
-        assert (got["accepted_len"][b], got["rejected"][b], got["out_token"][b]) == (0, 1, -1)
-    keep = np.array([b not in (2, 5) for b in range(w.B)])
-    for k in ("accepted_len", "rejected", "out_token", "status"):
-        assert (got[k][keep] == clean[k][keep]).all(), k
+    clean = gpu_step(ctx, inputs, 2, 2)
+    n, rej = clean["accepted_len"], clean["rejected"]
+    seen_row = _first((rej == 1) & (n >= 1))          # row 1 is examined
+    unseen_row = _first((rej == 1) & (n == 0))        # row 1 is not
+    seen_bonus = _first(rej == 0)                     # bonus row is drawn from
+    unseen_bonus = _first((rej == 1) & (np.arange(w.B) != seen_row) & (np.arange(w.B) != unseen_row))
+    seen_tok = _first((n >= 2) & ~np.isin(np.arange(w.B), [seen_row, seen_bonus]))   # position 1 is tested
+    unseen_tok = _first((rej == 1) & (n <= 1) & ~np.isin(np.arange(w.B), [seen_row, unseen_row, unseen_bonus]))
+    bad = dict(inputs, logits=inputs["logits"].clone(), draft_tokens=inputs["draft_tokens"].clone())
+    bad["logits"][seen_row * (g + 1) + 1, 17] = float("nan")
+    bad["logits"][unseen_row * (g + 1) + 1, 17] = float("nan")
+    bad["logits"][seen_bonus * (g + 1) + g, 4000] = float("inf")
+    bad["logits"][unseen_bonus * (g + 1) + g, 4000] = float("inf")
+    bad["draft_tokens"][seen_tok * g + 1] = w.V
+    bad["draft_tokens"][unseen_tok * g + 2] = -3
+    flagged = {seen_row: D.SESSION_BAD_ROW, seen_bonus: D.SESSION_BAD_ROW, seen_tok: D.SESSION_BAD_TOKEN}
+    keep = np.array([b not in flagged for b in range(w.B)])
+
+    def run(fn, flags=0):
+        t, out = D.alloc_out(bad, DEV)
+        fn(D.make_batch(bad, seed=2, step=2, flags=flags), out)
+        torch.cuda.synchronize()
+        return {k: v.cpu().numpy() for k, v in t.items()}
+
+    try:
+        D.dssd_set_fused_limit(ctx.handle, -(1 << 30))          # whole-step call as one launch
+        single = run(ctx.step_fused)
+        D.dssd_set_fused_limit(ctx.handle, 0)
+        D.dssd_set_fused_pair_limit(ctx.handle, 0)              # whole-step call on the streaming kernels
+        streamed = run(ctx.step_fused)
+        D.dssd_set_early_exit_schedule(ctx.handle, (0, 1, 2))
+        early = run(ctx.step_fused, D.FLAG_EARLY_EXIT)
+    finally:
+        D.dssd_set_early_exit_schedule(ctx.handle, ())
+        D.dssd_set_fused_limit(ctx.handle, 512)
+        D.dssd_set_fused_pair_limit(ctx.handle, 512)
+    for name, got in (("three calls", run(ctx.step)), ("single launch", single), ("streamed", streamed),
+                      ("early exit", early)):
+        for b, bit in flagged.items():
+            assert got["status"][b] == bit, (name, b, got["status"][b])
+            assert (got["accepted_len"][b], got["rejected"][b], got["out_token"][b]) == (0, 1, -1), (name, b)
+        for k in ("accepted_len", "rejected", "out_token", "status"):
+            assert (got[k][keep] == clean[k][keep]).all(), (name, k)
 
 
 SPARSE_CASES = [w for w in SMALL if w.top_k] + [
@@ -872,7 +914,8 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other(ctx):
 def test_early_exit_never_touches_rows_after_the_stopping_block(ctx):
     """Rows after the block that holds a session's first rejection are poisoned with NaN: the
     early-exit rounds still give the clean batch's records and tokens (those rows are never
-    used), while the default path, which reads every row, reports the sessions as bad."""
+    read), and so does the default path, which reads every row but, like Algorithm 2's loop,
+    looks at nothing after the first rejection."""
     w = synth.Workload("ee_poison", B=50, V=6000, gamma=0, dtype="bf16", gamma_range=(4, 14), sigmas=(0.5, 1.5))
     inputs = synth.generate(w, seed=41, device=DEV)
     clean = gpu_step(ctx, inputs, 8, 2)
@@ -900,7 +943,8 @@ def test_early_exit_never_touches_rows_after_the_stopping_block(ctx):
     for key in ("accepted_len", "rejected", "out_token", "status"):
         assert (clean[key] == t[key].cpu().numpy()).all(), key
     full = gpu_step(ctx, poisoned, 8, 2)
-    assert all(full["status"][b] & D.SESSION_BAD_ROW for b in hit)
+    for key in ("accepted_len", "rejected", "out_token", "status"):
+        assert (clean[key] == full[key]).all(), key
 
 
 def test_early_exit_rounds_inside_a_hip_graph(ctx):

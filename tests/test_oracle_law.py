@@ -336,8 +336,21 @@ def test_one_hot_draft_on_unlikely_token_and_bad_tokens():
         assert abs(r["resid_mass"] - 1.0) < 1e-12
         seen.add(int(r["token"]))
     assert len(seen) == V - 1
+    # a draft token outside the vocabulary is malformed input where the loop meets it ...
+    out = O.verify_batch(z, O.F32, Q, np.array([V, 5], np.int32), V, gamma=gamma, seed=1, step=0)
+    r = out["res"][0]
+    assert r["status"] & 1 and (r["n"], r["rejected"], r["token"]) == (0, 1, -1)
+    # ... also after accepted drafts (q = 0 at the first draft token: always accepted) ...
+    Q2 = Q.copy(); Q2[0, :] = 1.0 / (V - 1); Q2[0, 3] = 0.0
+    out = O.verify_batch(z, O.F32, Q2, np.array([3, -1], np.int32), V, gamma=gamma, seed=1, step=0)
+    r = out["res"][0]
+    assert r["status"] & 1 and (r["n"], r["rejected"], r["token"]) == (0, 1, -1)
+    # ... and is never looked at once a draft before it has been rejected (Algorithm 2: while Flag = 1)
+    good = O.verify_batch(z, O.F32, Q, np.array([5, 5], np.int32), V, gamma=gamma, seed=1, step=0)["res"][0]
     out = O.verify_batch(z, O.F32, Q, np.array([5, V], np.int32), V, gamma=gamma, seed=1, step=0)
-    assert out["res"][0]["status"] & 1 and out["res"][0]["token"] == -1
+    r = out["res"][0]
+    assert r["status"] == 0 and (r["n"], r["rejected"], r["token"]) == (0, 1, good["token"])
+    assert out["p_tok"][1] == 0.0 and out["q_tok"][1] == 0.0
 
 
 def test_top_k_truncated_supports():
