@@ -549,10 +549,11 @@ static dssd_status step_fused_launches(dssd_ctx* c, const dssd_batch* b, dssd_ou
   const bool bf16 = b->logits_dtype == DSSD_BF16, al = vector_ok(b);
   {
     Timed t(c, DSSD_K_FUSED_STEP, s);
-    const unsigned grid = (unsigned)(groups * b->B);
-    const int32_t g32 = (int32_t)groups;
+    const int32_t g32 = (int32_t)(((int64_t)(b->gamma + 1) * v.C + kFusedWaves - 1) / kFusedWaves);
+    const unsigned grid = (unsigned)((int64_t)g32 * b->B);
     with_flags([&](auto BF, auto AL, auto TR) {
-      DSSD_LAUNCH((fused_small_step<FLAG(BF), FLAG(AL), FLAG(TR)>), grid, s, v, g32, c->arrive_stats);
+      DSSD_LAUNCH_WG((fused_small_step<FLAG(BF), FLAG(AL), FLAG(TR)>), grid, kFusedWaves * kWave, 0, s, v, g32,
+                     c->arrive_stats);
     }, bf16, al, single);
   }
   if (pair && b->total_drafts > 0) {

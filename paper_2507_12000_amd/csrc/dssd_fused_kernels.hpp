@@ -3,11 +3,11 @@
 // has only a few thousand chunks the step is bound by launch latency, not by HBM, so the five
 // kernels of the streaming path are chained inside one launch:
 //
-//   every workgroup   : softmax statistics of up to four chunks of its session's rows, published
+//   every workgroup   : softmax statistics of up to sixteen chunks of its session's rows, published
 //                       with device-coherent stores; then it bumps the session's arrival counter;
 //   the workgroup that arrives last for a session goes on alone (no workgroup ever waits):
 //                       merges the rows, runs the accept / first-reject scan, and either
-//                       - computes the residual chunk masses of the rejected row with its four
+//                       - computes the residual chunk masses of the rejected row with its
 //                         waves and draws the token, or
 //                       - draws the bonus token from the chunk statistics.
 // Results are bit-identical to the three-call path: the same device functions in the same order.
@@ -16,18 +16,26 @@
 
 namespace dssd {
 
+// Workgroups of kFusedWaves waves: the lone workgroup that finishes a session streams the
+// rejected row with all of them, which is what bounds the step (16 waves cover a row of 16
+// chunks in one round trip; with 4 the same row took four).
+constexpr int kFusedWaves = 16;
+constexpr int kFusedMassSlots = 64;   // chunk masses kept in LDS when a row has at most this many chunks
+
 // TAIL_RESID = false leaves the redraw of rejected sessions to a following resid_mass launch
 // (rows too long for one workgroup to stream alone): two launches instead of four.
 template <bool BF16, bool ALIGNED, bool TAIL_RESID>
-__global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32_t groups, int32_t* arrive_stats) {
+__global__ __launch_bounds__(kFusedWaves * kWave) void fused_small_step(const BatchView a, int32_t groups,
+                                                                        int32_t* arrive_stats) {
   __shared__ int32_t sh_last;
+  __shared__ float sh_mass[kFusedMassSlots];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int32_t b = blockIdx.x / groups;
   const int32_t j = blockIdx.x - b * groups;
   const int32_t g = a.gamma;                         // uniform gamma only
   const int64_t lrow0 = (int64_t)b * (g + 1);
   const int32_t ntask = (g + 1) * a.C;               // chunk tasks of this session
-  const int32_t t = j * 4 + wave;
+  const int32_t t = j * kFusedWaves + wave;
   if (t < ntask) {
     const int32_t i = t / a.C, c = t - i * a.C;
     auto c1_of = [&]() { return (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e; };
@@ -49,13 +57,17 @@ __global__ __launch_bounds__(256) void fused_small_step(const BatchView a, int32
   const int32_t kind = accept_session<BF16>(a, b, &job);
   if (kind == 1) {
     if constexpr (!TAIL_RESID) return;
-    for (int32_t c = wave; c < a.C; c += 4) {
-      const float m = resid_chunk_mass<BF16, ALIGNED>(a, b, job, c, lane);
-      if (lane == 0) publish(a.resid_mass + (int64_t)b * a.C + c, m);
+    const bool in_lds = a.C <= kFusedMassSlots;
+    for (int32_t c = wave; c < a.C; c += kFusedWaves) {
+      const float m = resid_chunk_mass<BF16, ALIGNED, kUnroll>(a, b, job, c, lane);
+      if (lane == 0) {
+        if (in_lds) sh_mass[c] = m;
+        else publish(a.resid_mass + (int64_t)b * a.C + c, m);
+      }
     }
-    if (lane == 0) stores_done();
+    if (!in_lds && lane == 0) stores_done();
     __syncthreads();
-    if (wave == 0) pick_for_session<BF16, ALIGNED, true>(a, b, job, lane);
+    if (wave == 0) pick_for_session<BF16, ALIGNED, true>(a, b, job, lane, in_lds ? sh_mass : nullptr);
   } else if (kind == 2) {
     if (wave == 0) pick_for_session<BF16, ALIGNED, false>(a, b, job, lane);
   }

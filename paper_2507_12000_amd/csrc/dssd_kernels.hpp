@@ -218,8 +218,8 @@ __device__ __forceinline__ float2 merge_row_wave(const float2* cs, int32_t C, in
   return make_float2(M2, Z);
 }
 
-// One 256-thread workgroup per session.  The four waves merge the session's rows (four rows
-// per wave in flight at a time); wave 0 then takes lane i = draft position i.
+// One workgroup per session.  Its waves merge the session's rows (four rows per wave in flight
+// at a time); wave 0 then takes lane i = draft position i.
 // Returns (to every thread of the workgroup) what the session has to draw next: kind 1 = redraw
 // from the residual at job.lrow, kind 2 = bonus token from job.lrow, 0 = nothing (device-side
 // error).  Chunk pairs are read with device-coherent loads, so the caller may be the launch that
@@ -237,6 +237,7 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, i
   __shared__ Job sh_job;
   __shared__ int32_t sh_kind;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int32_t nwaves = (int32_t)(blockDim.x >> 6);   // each row is merged by one wave, whatever their number
   const int64_t off0 = session_first_draft(a, b);
   const int64_t off1 = a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma;
   int32_t bad = 0;
@@ -268,17 +269,17 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, i
           q = a.q_scalars ? a.q_scalars[qrow] : a.draft_probs[qrow * (int64_t)a.V + x];
         }
       }
-      for (int32_t r0 = wave; r0 < nrows; r0 += 16) {
+      for (int32_t r0 = wave; r0 < nrows; r0 += 4 * nwaves) {
         float2 first[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int32_t r = r0 + 4 * j;
+          const int32_t r = r0 + nwaves * j;
           first[j] = (r < nrows && lane < a.C) ? observe2(a.chunk_stats + (lrow0 + base + r) * a.C + lane)
                                                : make_float2(neg_inf(), 0.f);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int32_t r = r0 + 4 * j;
+          const int32_t r = r0 + nwaves * j;
           if (r < nrows) {
             const int64_t lrow = lrow0 + base + r;
             const float2 st = merge_row_wave(a.chunk_stats + lrow * a.C, a.C, lane, first[j]);
@@ -425,12 +426,16 @@ struct LogitWeights {
 };
 
 template <bool BF16, bool ALIGNED, bool RESID>
-__device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, int lane);
+__device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, int lane,
+                                 const float* lds_mass = nullptr);
 
 // Residual resample (Algorithm 2 "Resample"): mass of max(0, P - Q) per chunk of the rejected
 // row, one wave per chunk.  Sessions that were not rejected exit at once.  FUSE_PICK: the last
 // workgroup of a session to finish also draws the token, which saves the second launch.
-template <bool BF16, bool ALIGNED>
+// GROUPS_IN_FLIGHT (4 or 8) only sets how many of a lane's 8 groups are loaded before the sums
+// start on the path that loads 16-byte groups; the order of the sums, and so every bit of the
+// result, is the same.
+template <bool BF16, bool ALIGNED, int GROUPS_IN_FLIGHT = 4>
 __device__ __forceinline__ float resid_chunk_mass(const BatchView& a, int32_t b, const Job& job, int32_t c,
                                                   int lane) {
   constexpr int E = Elems<BF16>::per_vec;
@@ -473,18 +478,21 @@ __device__ __forceinline__ float resid_chunk_mass(const BatchView& a, int32_t b,
     }
   } else {
     // fp32 logits are 4 per 16-byte group, like Q: already one contiguous stretch per instruction.
-    // Two half-chunks of 4 groups each (unaligned rows take the scalar loads of load_logits).
+    // Streaming launches take two half-chunks of 4 groups each (measured faster than all 8 at
+    // once there); a lone workgroup finishing a session takes all 8 (one round trip fewer).
+    // Unaligned rows take the scalar loads of load_logits.
+    constexpr int G = GROUPS_IN_FLIGHT;
     const int64_t v0 = (int64_t)c * kChunkVecs + lane;
 #pragma unroll
-    for (int k0 = 0; k0 < kUnroll; k0 += 4) {
-      float z[4][E], q[4][E];
+    for (int k0 = 0; k0 < kUnroll; k0 += G) {
+      float z[G][E], q[G][E];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
+      for (int k = 0; k < G; ++k) {
         load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
         load_probs<E, ALIGNED>(qp, (v0 + (k0 + k) * kWave) * E, a.V, q[k]);
       }
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+      for (int k = 0; k < G; ++k)
 #pragma unroll
         for (int e = 0; e < E; ++e)
           acc += fmaxf(0.f, fmaf(fast_exp2(fmaf(z[k][e], c1, -st.x)), invZ, -q[k][e]));
@@ -640,8 +648,10 @@ __device__ __forceinline__ int32_t pick_chunk(MassFn mass, int32_t C, float r, i
 // One wave per session.  RESID: rejected sessions, row n, weights max(0, P - Q), r = word 1 of
 // the position-n block.  Otherwise: all-accepted sessions, row gamma_b, weights P, r = word 2 of
 // the position-gamma_b block (Algorithm 2: "Sample x_{gamma+1} ~ P_{gamma+1}").
+// lds_mass: the session's residual chunk masses in LDS when the calling workgroup has just
+// computed them itself (same values as in a.resid_mass, two round trips to memory fewer).
 template <bool BF16, bool ALIGNED, bool RESID>
-__device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, int lane) {
+__device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, int lane, const float* lds_mass) {
   const int64_t lrow = job.lrow;
   const int32_t n = (int32_t)(lrow - b - session_first_draft(a, b));   // position inside the session
   const float2 st = make_float2(job.M2, job.Z);
@@ -660,7 +670,8 @@ __device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, 
   bool from_p = !RESID;
   if constexpr (RESID) {
     const float* rm = a.resid_mass + (int64_t)b * a.C;
-    const int32_t c = pick_chunk([&](int32_t cc) { return observe(rm + cc); }, a.C, r, lane, &target, &total);
+    const int32_t c = pick_chunk([&](int32_t cc) { return lds_mass ? lds_mass[cc] : observe(rm + cc); }, a.C, r,
+                                 lane, &target, &total);
     if (c >= 0) token = pick_in_chunk(LogitWeights<BF16, ALIGNED, true>{lp, qp, a.V, c1, st.x, invZ}, c, target, lane);
     if (token < 0) from_p = true;   // residual mass rounded to zero: draw from P_n instead
   }
