@@ -21,15 +21,15 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM bytes per launch of row_chunk_stats from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
-# what the same counters read for a plain copy of known size; profiles/row_chunk_stats_cfg4_pmc.txt).
+# what the same counters read for a plain copy of known size; profiles/step_cfg4_hbm_bytes_pmc.txt).
 # Taken in profiler runs of their own, not in the run that prints them, and valid only for the
 # sources they were taken with: reported as null once any file the kernel and its launch are made
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "6eac15ab4213c4bb38360e712234c6b7b52efc319e3912c81d5cb5596ab3358d",
-        "bytes_per_launch": int((2426304.1 * 2.0 + 4776.7 * 1.0) * 1024),
-        "source": "profiles/row_chunk_stats_cfg4_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
+        "sources_sha256": "bdc9b6ea8483a6eab3fc5fb2182a170d14072a07a859a45047bbb014479fd35e",
+        "bytes_per_launch": int((2426292.9 * 2.0 + 4776.7 * 1.0) * 1024),
+        "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }
 KERNEL_SOURCES = ("dssd_device.hpp", "dssd_kernels.hpp", "dssd.hip")   # what row_chunk_stats and its launch are made of
