@@ -1,6 +1,8 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
 on the same seeded inputs.  Bit-exact accepted_len / rejected / out_token outside counted
-near-ties; p_i(x_i) and the row log-sum-exp within 1e-5 (fp32 logits) or 2e-3 (bf16 logits)."""
+near-ties; p_i(x_i) and the row log-sum-exp within 1e-5 relative, for fp32 and for bf16 logits
+alike: both sides widen the same stored bf16 values exactly and the kernels compute in fp32, so
+the benchmark definition's looser 2e-3 for bf16 is a ceiling this suite does not need."""
 import ctypes
 
 import numpy as np
@@ -15,7 +17,7 @@ from paper_2507_12000_amd import synth          # noqa: E402
 import parity                                   # noqa: E402
 
 DEV = "cuda:0"
-P_RTOL = {"f32": 1e-5, "bf16": 2e-3}
+P_RTOL = {"f32": 1e-5, "bf16": 1e-5}
 
 
 @pytest.fixture(scope="module")
