@@ -39,7 +39,8 @@ MUTATIONS = {
     "margin_sign_kept": ("const double gap = std::fabs(r * q - p);", "const double gap = r * q - p;"),
     "margin_divides_by_p": ("return q > 0.0 ? gap / q :", "return q > 0.0 ? gap / p :"),
     "margin_counts_positions_after_the_rejection": ("    if (!open) continue;\n", ""),
-    "bad_token_never_reported": ("    if (!in_vocabulary) {  // malformed input met by the loop", "    if (false) {"),
+    "bad_token_never_reported": ("    if (!in_vocabulary) {  // malformed input met by the loop: report, emit nothing\n      open = false;",
+                                 "    if (false) {\n      open = false;"),
     "stops_one_late": ("open = false;  // Flag = 0\n      res->n = i;",
                        "open = false;  // Flag = 0\n      res->n = i + 1 < gamma ? i + 1 : i;"),
 }
