@@ -476,8 +476,11 @@ def main():
         torch.cuda.synchronize()
         if D.dssd_profile_read(ctx.handle, D.K_FUSED_STEP)[1]:
             dom_id = D.K_FUSED_STEP
+    # (with early exit the library may decide that the batch is too small for it and run the
+    # default kernels: whichever statistics kernel was launched is the one that is reported)
+    cands = [D.K_ROW_STATS_BLOCK, D.K_ROW_STATS, D.K_FUSED_STEP] if args.early_exit else [dom_id]
     D.dssd_profile_reset(ctx.handle)
-    D.dssd_profile_enable(ctx.handle, 1 << dom_id)
+    D.dssd_profile_enable(ctx.handle, sum(1 << k for k in cands))
     t0 = time.perf_counter()
     for k in range(args.steps):
         batch.step = args.warmup + k
@@ -485,6 +488,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     D.dssd_profile_enable(ctx.handle, False)
+    dom_id = next(k for k in cands if D.dssd_profile_read(ctx.handle, k)[1] > 0)
     dom_ms, dom_n = D.dssd_profile_read(ctx.handle, dom_id)
     assert dom_n == args.steps or (args.early_exit and dom_n % args.steps == 0)
     dom_per_step = dom_n // args.steps     # early exit: the statistics kernel runs once per round

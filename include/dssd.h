@@ -76,8 +76,10 @@ enum {
    * gamma and Flag = 1") at its word and read a session's logits rows only about as far as its
    * first rejected draft.  The rows are visited in rounds of growing blocks (by default [0,2),
    * [2,6), the rest; two blocks [0,3), the rest for smaller batches; none where the extra
-   * launches are expected to cost more than the unread rows save), and a session leaves as soon as a block holds its first rejection or
-   * its bonus row.  accepted_len, rejected and out_token are bit-identical to the default path,
+   * launches are expected to cost more than the unread rows save: the choice prices unread rows at
+   * a per-position acceptance of 0.8 against 140 MB of streaming per extra round, figures tuned
+   * on MI355X; dssd_set_early_exit_schedule of dssd_aux.h overrides it), and a session leaves as
+   * soon as a block holds its first rejection or its bonus row.  accepted_len, rejected and out_token are bit-identical to the default path,
    * and so are row_stats, p_tok and q_tok for the rows and positions of the blocks that were
    * visited; entries of later blocks are NaN.  Honoured by dssd_verify_batch and
    * dssd_step_fused; combines with DSSD_FLAG_SPARSE_SUPPORT. */
@@ -170,13 +172,15 @@ dssd_status dssd_bonus_sample(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *
 
 /* The whole step in one call, as in Algorithm 1 where the edge does all of it: equivalent to
  * dssd_verify_batch, dssd_residual_sample, dssd_bonus_sample in a row on the same stream, with
- * bit-identical outputs.  Batches with uniform gamma (draft_offsets == NULL) whose grid is small
- * (at most 512 workgroups unless dssd_set_fused_limit of dssd_aux.h says otherwise) and whose rows are
- * short (V * (logit bytes + 4) <= 384 KiB) run as ONE kernel launch, which is what matters when
- * a step is bound by launch latency rather than bandwidth; small grids with longer rows run as
- * TWO launches (statistics + accept + bonus, then the redraw of rejected sessions); all others
- * run the kernels of the three calls, with the bonus draw folded into the accept launch when
- * the rows are dense (one launch fewer).  Needs the full Q rows (draft_probs). */
+ * bit-identical outputs.  Batches with uniform gamma (draft_offsets == NULL) that are small
+ * (B * ceil((gamma+1) * chunks_per_row / 4) <= 512 unless dssd_set_fused_limit of dssd_aux.h says
+ * otherwise; a chunk is 8 KiB of logits) and whose rows are short (V * (logit bytes + 4) <= 384
+ * KiB: what one workgroup streams quickly when it finishes a session alone) run as ONE kernel
+ * launch, which is what matters when a step is bound by launch latency rather than bandwidth;
+ * small batches with longer rows run as TWO launches (statistics + accept + bonus, then the
+ * redraw of rejected sessions); all others run the kernels of the three calls, with the bonus
+ * draw folded into the accept launch when the rows are dense (one launch fewer).  Needs the full
+ * Q rows (draft_probs). */
 dssd_status dssd_step_fused(dssd_ctx *ctx, const dssd_batch *batch, dssd_out *out, void *hip_stream);
 /* The whole step for callers that cannot allocate device memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and bit-identical

@@ -13,16 +13,18 @@ extern "C" {
 
 /* ---- tuning knobs (per context; defaults suit MI355X) ---- */
 
-/* Largest grid (workgroups = B * ceil((gamma+1) * chunks_per_row / 4)) that dssd_step_fused runs
- * as a single launch; 0 disables the single-launch path; a negative value sets the limit to its
- * magnitude and lifts the row-length rule (for tests and measurements). */
+/* Largest batch, counted as B * ceil((gamma+1) * chunks_per_row / 4), that dssd_step_fused runs
+ * as a single launch (default 512: beyond it the streaming kernels were measured faster on
+ * MI355X); 0 disables the single-launch path; a negative value sets the limit to its magnitude
+ * and lifts the row-length rule (for tests and measurements). */
 dssd_status dssd_set_fused_limit(dssd_ctx *ctx, int64_t max_blocks);
 /* Blocks of DSSD_FLAG_EARLY_EXIT: begin[0..n) are the first rows of the blocks, strictly
  * increasing from begin[0] = 0, the last block open-ended; n in [2, 8] (one block would be the
  * default path).  n = 0 returns to the automatic choice by batch size. */
 dssd_status dssd_set_early_exit_schedule(dssd_ctx *ctx, const int32_t *begin, int32_t n);
-/* Largest grid that dssd_step_fused runs as two launches when the single-launch rule does not
- * apply; 0 disables the two-launch path.  Negative values are DSSD_EINVAL. */
+/* Largest batch (counted the same way, default 512) that dssd_step_fused runs as two launches
+ * when the single-launch rule does not apply; 0 disables the two-launch path.  Negative values
+ * are DSSD_EINVAL. */
 dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
 
 /* Waves per compute unit that the two streaming kernels (row statistics; residual masses) keep

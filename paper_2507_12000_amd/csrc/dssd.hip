@@ -471,10 +471,10 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   // draws the token.  Many: the arrival (a store that must be acknowledged, a barrier, an atomic
   // that must return) holds every workgroup's wave slots a few microseconds longer with nothing
   // in flight, which costs a streaming kernel more than the second launch does.
-#ifndef DSSD_RESID_FUSE_LIMIT
-#define DSSD_RESID_FUSE_LIMIT 1024
-#endif
-  const bool fuse = (int64_t)grid <= DSSD_RESID_FUSE_LIMIT;
+  // (swept on the benchmark workloads: folding wins up to about a thousand workgroups and loses
+  // from two thousand on)
+  constexpr int64_t kResidFuseLimit = 1024;
+  const bool fuse = (int64_t)grid <= kResidFuseLimit;
   {
     Timed t(c, DSSD_K_RESID_MASS, s);
     with_flags([&](auto BF, auto AL, auto FP) {

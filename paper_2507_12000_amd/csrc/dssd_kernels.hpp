@@ -609,9 +609,12 @@ template <typename MassFn>
 __device__ __forceinline__ int32_t pick_chunk(MassFn mass, int32_t C, float r, int lane, float* target_in_chunk,
                                               float* total_out) {
   float run = 0.f;
+  float m_first = 0.f, sc_first = 0.f;   // the first batch (the only one when C <= 64) is kept for the second pass
   for (int32_t base = 0; base < C; base += kWave) {
     const int32_t c = base + lane;
-    const float sc = wave_scan(c < C ? mass(c) : 0.f, lane);
+    const float m = c < C ? mass(c) : 0.f;
+    const float sc = wave_scan(m, lane);
+    if (base == 0) { m_first = m; sc_first = sc; }
     run = run + lane_value(sc, 63);
   }
   *total_out = run;
@@ -622,8 +625,8 @@ __device__ __forceinline__ int32_t pick_chunk(MassFn mass, int32_t C, float r, i
   float before_last = 0.f;
   for (int32_t base = 0; base < C; base += kWave) {
     const int32_t c = base + lane;
-    const float m = c < C ? mass(c) : 0.f;
-    const float sc = wave_scan(m, lane);
+    const float m = base == 0 ? m_first : (c < C ? mass(c) : 0.f);
+    const float sc = base == 0 ? sc_first : wave_scan(m, lane);
     // a chunk of zero mass can sit one rounding above its predecessor in the scan: never taken
     const uint64_t weighty = __ballot(m > 0.f);
     const uint64_t over = __ballot((run + sc) > t && m > 0.f);

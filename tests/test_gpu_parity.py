@@ -982,3 +982,39 @@ def test_early_exit_rounds_inside_a_hip_graph(ctx):
                 assert (got[k] == want[k]).all(), (k, rep)
     finally:
         D.dssd_set_early_exit_schedule(ctx.handle, ())
+
+
+def test_occupancy_caps_change_speed_not_results(ctx):
+    """The caps on resident waves (LDS the streaming kernels never touch) act on grids of at
+    least 16 workgroups per compute unit: on such a batch every cap, and none, gives the same bits,
+    and the oracle agrees on a sample of the sessions."""
+    w = synth.Workload("caps", B=96, V=4096 * 24, gamma=7, dtype="bf16", sigmas=(1.0, 2.0))   # 768 rows x 24 chunks
+    inputs = synth.generate(w, seed=6, device=DEV)
+    assert inputs["R_L"] * 24 // 4 >= 16 * 256
+    ref = gpu_step(ctx, inputs, 12, 1)
+    try:
+        for stats_cap, resid_cap in ((0, 0), (8, 8), (12, 16), (24, 4), (64, 64)):
+            assert D.dssd_set_stream_occupancy(ctx.handle, stats_cap, resid_cap) == D.DSSD_OK
+            got = gpu_step(ctx, inputs, 12, 1)
+            for k in ref:
+                assert (got[k] == ref[k]).all() or np.array_equal(got[k], ref[k], equal_nan=True), (stats_cap, resid_cap, k)
+        assert D.dssd_set_stream_occupancy(ctx.handle, -1, 0) == D.DSSD_EINVAL
+    finally:
+        D.dssd_set_stream_occupancy(ctx.handle, 16, 8)
+    h = parity.to_numpy_inputs(inputs)
+    orc = parity.run_oracle(h, 12, 1, workers=16, sessions=np.arange(0, w.B, 6))
+    parity.compare(h, ref, orc, 1e-5, seed=12, step=1)
+
+
+def test_read_probe_variants_run_and_bad_ones_are_refused(ctx):
+    buf = torch.zeros(64 << 20, dtype=torch.uint8, device=DEV)   # 64 MiB: 16 384 workgroups at 1 load per lane
+    for loads in (1, 2, 4, 8):
+        for cap in (0, 8, 16):
+            D.dssd_probe_read(ctx.handle, buf.data_ptr(), buf.numel(), loads, cap, ctx.stream())
+    torch.cuda.synchronize()
+    lib = D.load()
+    import ctypes as C
+    assert lib.dssd_probe_read(ctx.handle, C.c_void_p(buf.data_ptr()), buf.numel(), 3, 0, None) == D.DSSD_EINVAL
+    assert lib.dssd_probe_read(ctx.handle, C.c_void_p(buf.data_ptr()), buf.numel(), 8, -1, None) == D.DSSD_EINVAL
+    assert lib.dssd_probe_read(ctx.handle, C.c_void_p(buf.data_ptr() + 4), 1 << 20, 8, 0, None) == D.DSSD_EALIGN
+    assert lib.dssd_probe_read(ctx.handle, C.c_void_p(buf.data_ptr()), 100, 8, 0, None) == D.DSSD_OK   # less than one wave's share
