@@ -288,3 +288,64 @@ def test_edge_with_early_exit_exports_the_same_rows(ctx):
     assert (tok0[rej == 0] == tok1[rej == 0]).all()          # bonus tokens
     assert torch.equal(p0, p1)                               # downlink payload
     assert torch.isnan(t1["row_stats"]).any()                # rows really were skipped
+
+
+def _dpp_prefix_sums(x):
+    """The kernels' 64-lane inclusive prefix sum, in their order of additions and in fp32: four
+    shifted adds inside each row of 16 lanes, then lane 15 of rows 0 and 2 added to rows 1 and 3,
+    then lane 31 added to the upper half.  Each lane sums a tree of its own, so the result need
+    not be monotone across lanes."""
+    x = x.astype(np.float32).copy()
+    idx = np.arange(64)
+    for d in (1, 2, 4, 8):
+        src = np.where(idx % 16 >= d, x[np.maximum(idx - d, 0)], np.float32(0))
+        x = (x + src).astype(np.float32)
+    add = np.zeros(64, np.float32); add[16:32] = x[15]; add[48:64] = x[47]
+    x = (x + add).astype(np.float32)
+    add = np.zeros(64, np.float32); add[32:64] = x[31]
+    return (x + add).astype(np.float32)
+
+
+def test_zero_weight_tokens_are_never_drawn_at_a_rounding_inversion(ctx):
+    """A parallel prefix sum can put a lane of zero weight one rounding ABOVE its predecessor.  A
+    threshold search that looked at the sums alone would then draw a token of weight zero for the
+    few uniforms that fall in that gap -- a token the residual law of Algorithm 2 ("Resample")
+    gives probability 0.  Rows chosen (by the emulation above) to have many such gaps, sixteen
+    million draws over them through the device-side redraw, whose weights max(0, P - Q) the test
+    sets exactly (Q = 0): every token drawn carries weight."""
+    V, B, steps = 512, 1 << 16, 256
+    rows = []
+    for seed in (980596406, 1381852826, 514218545, 87766757):
+        g = np.random.default_rng(seed)
+        lane = np.exp(g.normal(0, 3, 64)).astype(np.float32)
+        lane[g.random(64) < 0.5] = 0
+        s = _dpp_prefix_sums(lane)
+        gaps = sum(1 for j in range(1, 64) if lane[j] == 0 and s[j] > s[j - 1])
+        assert gaps >= 8, (seed, gaps)              # the row is of the dangerous kind
+        row = np.zeros(V, np.float32)
+        row[0::8] = lane                             # lane j's group of 8 entries: all its weight on the first
+        rows.append(row / np.float32(lane.sum() * 1.5))   # a distribution's scale; the rest of the mass is absent
+    P = torch.from_numpy(np.stack(rows)).to(DEV)
+    p_rows = P.repeat(B // 4, 1).contiguous()        # session b uses row b % 4
+    weight = (p_rows > 0)
+    inputs = dict(B=B, V=V, gamma=1, R_Q=B, R_L=2 * B, draft_offsets=None,
+                  draft_probs=torch.zeros((B, V), dtype=torch.float32, device=DEV))
+    n = torch.zeros(B, dtype=torch.int32, device=DEV)
+    rejected = torch.ones(B, dtype=torch.int32, device=DEV)
+    out_token = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    status = torch.zeros(B, dtype=torch.int32, device=DEV)
+    big = D.Context(DEV, max_rows=B, max_V=V)
+    try:
+        seen = torch.zeros(V, dtype=torch.int64, device=DEV)
+        for step in range(steps):
+            db = D.make_device_batch(inputs, p_rows, n, rejected, out_token, status, seed=2024, step=step)
+            D.dssd_residual_sample_from_p(big.handle, db, big.stream())
+            tok = out_token.long()
+            assert bool(((tok >= 0) & (tok < V)).all()) and int(status.abs().sum()) == 0, step
+            assert bool(weight[torch.arange(B, device=DEV), tok].all()), f"a zero-weight token was drawn at step {step}"
+            seen += torch.bincount(tok, minlength=V)
+        # and the draws follow the weights (coarse: every weighty token of row 0 above 1e-4 was seen)
+        heavy = (P[0] / P[0].sum()) > 1e-4
+        assert bool((seen[heavy] > 0).all())
+    finally:
+        big.close()
