@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "bdc9b6ea8483a6eab3fc5fb2182a170d14072a07a859a45047bbb014479fd35e",
-        "bytes_per_launch": int((2426292.9 * 2.0 + 4776.7 * 1.0) * 1024),
+        "sources_sha256": "a60b9474e423c42d567906eaa502e796e546ce8cfb6881fdc95f5e1c74e8534f",
+        "bytes_per_launch": int((2426293.2 * 2.0 + 4776.7 * 1.0) * 1024),
         "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }

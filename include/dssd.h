@@ -20,6 +20,8 @@
  *     from, its softmax statistics) that verify left in the context's workspace, not on the
  *     caller's copies of accepted_len / rejected.
  *   - One context serves one stream at a time (its workspace is shared by consecutive calls).
+ *     A context belongs to the device it was created on: that device must be the current one
+ *     when its calls are made (dssd_create itself leaves the caller's current device as it was).
  *   - Positions are 0-based: accepted_len = j - 1 in the paper's numbering.
  *   - Host-checkable errors return a negative status before anything is launched.  Errors that
  *     only the device can see (token id outside [0,V), inconsistent offsets, a logits row whose

@@ -65,7 +65,7 @@ struct dssd_ctx {
   // towards full occupancy).  The caps below are waves per compute unit, enforced by asking for
   // LDS the kernels never touch; 0 = whatever the registers allow.
   int32_t stats_waves_per_cu = 16;
-  int32_t resid_waves_per_cu = 8;
+  int32_t resid_waves_per_cu = 16;
   int64_t max_rows = 0;
   int32_t max_V = 0;
   int32_t max_C = 0;

@@ -1000,7 +1000,7 @@ def test_occupancy_caps_change_speed_not_results(ctx):
                 assert (got[k] == ref[k]).all() or np.array_equal(got[k], ref[k], equal_nan=True), (stats_cap, resid_cap, k)
         assert D.dssd_set_stream_occupancy(ctx.handle, -1, 0) == D.DSSD_EINVAL
     finally:
-        D.dssd_set_stream_occupancy(ctx.handle, 16, 8)
+        D.dssd_set_stream_occupancy(ctx.handle, 16, 16)
     h = parity.to_numpy_inputs(inputs)
     orc = parity.run_oracle(h, 12, 1, workers=16, sessions=np.arange(0, w.B, 6))
     parity.compare(h, ref, orc, 1e-5, seed=12, step=1)
