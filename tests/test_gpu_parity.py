@@ -1018,3 +1018,43 @@ def test_read_probe_variants_run_and_bad_ones_are_refused(ctx):
     assert lib.dssd_probe_read(ctx.handle, C.c_void_p(buf.data_ptr()), buf.numel(), 8, -1, None) == D.DSSD_EINVAL
     assert lib.dssd_probe_read(ctx.handle, C.c_void_p(buf.data_ptr() + 4), 1 << 20, 8, 0, None) == D.DSSD_EALIGN
     assert lib.dssd_probe_read(ctx.handle, C.c_void_p(buf.data_ptr()), 100, 8, 0, None) == D.DSSD_OK   # less than one wave's share
+
+
+def _random_large_workload(k):
+    rng = np.random.default_rng(7000 + k)
+    dt = "bf16" if rng.integers(2) else "f32"
+    V = int(rng.choice([32000, 50257, 65536, 100003, 128256, 151936, 152064, 200000, 256000, 262144,
+                        4096 * 17 + 8, 2048 * 33 + 4]))
+    B, gmax = int(rng.integers(1, 97)), int(rng.integers(1, 17))
+    kw = dict(B=B, V=V, dtype=dt, zipf_s=float(rng.choice([0.8, 1.0, 1.2])),
+              sigmas=tuple(float(x) for x in rng.choice([0.25, 0.5, 1.0, 2.0], size=2)),
+              frac_q_equals_p=float(rng.choice([0, 0.1])), frac_q_uniform=float(rng.choice([0, 0.1])))
+    if rng.integers(2):
+        kw.update(gamma=0, gamma_range=(int(rng.integers(0, 2)), gmax))
+    else:
+        kw.update(gamma=gmax)
+    if rng.integers(3) == 0:
+        kw.update(temperature_range=(0.5, 1.6))
+    if rng.integers(5) == 0:
+        kw.update(top_k=int(rng.choice([1, 10, 50])))
+    return synth.Workload(f"large{k}_{dt}_V{V}_B{B}", **kw)
+
+
+@pytest.mark.parametrize("k", range(16))
+def test_random_large_shapes(ctx, k):
+    """Seeded random batches with the vocabularies of real models (32 000 ... 262 144, aligned and
+    not, fp32 and bf16, ragged, with temperature, truncated): oracle parity for the three calls,
+    and bit-equal outputs from the whole-step call and from the call on the static scratch array
+    (where the batch fits it)."""
+    w = _random_large_workload(k)
+    inputs, gpu, orc, rep = check(ctx, w, seed=k, step=k, workers=16, gen_seed=k)
+    t2, out2 = D.alloc_out(inputs, DEV)
+    ctx.step_fused(D.make_batch(inputs, seed=k, step=k), out2)
+    t3, out3 = D.alloc_out(inputs, DEV)
+    rc = D.dssd_step_static(D.make_batch(inputs, seed=k, step=k), out3, ctx.stream(), check=False)
+    torch.cuda.synchronize()
+    assert rc in (D.DSSD_OK, D.DSSD_ENOMEM)
+    for key in gpu:
+        assert np.array_equal(gpu[key], t2[key].cpu().numpy(), equal_nan=True), ("whole-step", key)
+        if rc == D.DSSD_OK:
+            assert np.array_equal(gpu[key], t3[key].cpu().numpy(), equal_nan=True), ("static", key)
