@@ -307,6 +307,29 @@ def test_extreme_shapes(ctx, w):
     check(ctx, w, seed=99, step=5, workers=16)
 
 
+HUGE_V = [
+    # a million-entry vocabulary in fp32: 513 chunks per row (nine batches of 64 in every merge and scan)
+    synth.Workload("f32_V1048584", B=2, V=(1 << 20) + 8, gamma=1, dtype="f32", sigmas=(1.0,)),
+    # two million entries in bf16, unaligned rows: the scalar-load instantiation over 513 chunks
+    synth.Workload("bf16_V2097155", B=2, V=(1 << 21) + 3, gamma=2, dtype="bf16", sigmas=(2.0,)),
+]
+
+
+@pytest.mark.parametrize("w", HUGE_V, ids=[w.name for w in HUGE_V])
+def test_vocabularies_far_beyond_any_model(w):
+    inputs = synth.generate(w, seed=2, device=DEV)
+    big = D.Context(DEV, max_rows=inputs["R_L"], max_V=w.V)
+    try:
+        _, gpu, _, rep = check(big, w, seed=5, step=9, workers=8, gen_seed=2)
+        t, out = D.alloc_out(inputs, DEV)
+        big.step_fused(D.make_batch(inputs, seed=5, step=9), out)
+        torch.cuda.synchronize()
+        for key in gpu:
+            assert np.array_equal(gpu[key], t[key].cpu().numpy(), equal_nan=True), key
+    finally:
+        big.close()
+
+
 def test_misaligned_base_pointers_take_the_scalar_path(ctx):
     """V is a multiple of 8 but the buffers start 4 bytes into a 16-byte line."""
     w = synth.Workload("shifted", B=6, V=8192 + 64, gamma=3, dtype="f32", sigmas=(1.0,))
