@@ -376,10 +376,11 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
       Timed t(c, DSSD_K_ROW_STATS_BLOCK, s);
       if (r == 0) {
         const int32_t w = std::min(end, known_rows);
+        if ((int64_t)b->B * w * v.C > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;   // 32-bit chunk indices
         const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
-        if (blocks > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;
         with_flags([&](auto BF, auto AL, auto SP) {
-          DSSD_LAUNCH((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, s, v, w, c->open_count, kMaxRounds);
+          DSSD_LAUNCH_WG((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, 256,
+                         occupancy_cap_lds(c, 4, c->stats_waves_per_cu, blocks), s, v, w, c->open_count, kMaxRounds);
         }, bf16, al, sparse);
       } else {
         // the rows listed by the accept launch before: at most every row that is left

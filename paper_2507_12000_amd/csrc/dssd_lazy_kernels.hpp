@@ -42,24 +42,28 @@ struct __attribute__((aligned(16))) RowTask {
 template <bool BF16, bool ALIGNED, bool SUPPORT>
 __global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, int32_t width, ListLengths* zero,
                                                             int32_t n_zero) {
+  // wave-uniform 32-bit arithmetic up to the loads, as in row_chunk_stats (the host refuses
+  // batches with 2^31 chunk tasks or more)
   const int lane = threadIdx.x & 63;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   if (blockIdx.x == 0 && threadIdx.x < n_zero) zero[threadIdx.x] = 0;
-  const int64_t per_session = (int64_t)width * a.C;
-  const int64_t task = xcd_contiguous(blockIdx.x, gridDim.x, a.xcds) * 4 + (threadIdx.x >> 6);
-  if (task >= a.B * per_session) return;
+  const uint32_t C = (uint32_t)a.C;
+  const uint32_t per_session = (uint32_t)width * C;
+  const uint32_t task = xcd_contiguous32(blockIdx.x, gridDim.x, a) * 4 + wave;
+  if (task >= (uint32_t)a.B * per_session) return;
   const int32_t b = (int32_t)(task / per_session);
-  const int32_t rem = (int32_t)(task - b * per_session);
-  const int32_t i = rem / a.C, c = rem - i * a.C;
+  const uint32_t rem = task - (uint32_t)b * per_session;
+  const int32_t i = (int32_t)(rem / C), c = (int32_t)(rem - (rem / C) * C);
   const int64_t off0 = session_first_draft(a, b);
   const int64_t off1 = a.offsets ? (int64_t)a.offsets[b + 1] : off0 + a.gamma;
   if (off0 < 0 || off1 < off0 || off1 > a.R_Q) return;   // reported by the accept launch
   if (i > off1 - off0) return;                            // the session has fewer rows
-  const float c1 = (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e;
   const int64_t lrow = off0 + b + i;
   SupportRow sup{};
   if constexpr (SUPPORT)
     sup = SupportRow{a.support_count + lrow, a.support_idx + lrow * kMaxSupport, a.support_z + lrow * kMaxSupport};
-  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, lrow), c, a.V, [=]() { return c1; }, lane, sup);
+  auto c1_of = [&]() { return (a.inv_temp ? a.inv_temp[b] : 1.f) * kLog2e; };
+  const float2 st = chunk_stats_of<BF16, ALIGNED, SUPPORT>(logits_row<BF16>(a, lrow), c, a.V, c1_of, lane, sup);
   if (lane == 0) a.chunk_stats[lrow * a.C + c] = st;
 }
 
@@ -69,16 +73,18 @@ template <bool BF16, bool ALIGNED, bool SUPPORT>
 __global__ __launch_bounds__(256) void row_chunk_stats_list(const BatchView a, const RowTask* rows,
                                                             const ListLengths* lengths) {
   const int lane = threadIdx.x & 63;
-  const int64_t total = (int64_t)listed_rows(*lengths) * a.C;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t C = (uint32_t)a.C;
+  const uint32_t total = (uint32_t)listed_rows(*lengths) * C;   // below 2^31: the listed rows are rows of the batch
   // each XCD walks one contiguous share of the list (the grid is a multiple of the XCD count)
   const uint32_t xcds = (uint32_t)a.xcds;
-  const int64_t nblk = (total + 3) / 4, per = (nblk + xcds - 1) / xcds;
-  const int64_t first = (int64_t)(blockIdx.x % xcds) * per;
-  for (int64_t k = blockIdx.x / xcds; k < per; k += gridDim.x / xcds) {
-    const int64_t task = (first + k) * 4 + (threadIdx.x >> 6);
+  const uint32_t nblk = (total + 3) / 4, per = (nblk + xcds - 1) / xcds;
+  const uint32_t first = (blockIdx.x % xcds) * per;
+  for (uint32_t k = blockIdx.x / xcds; k < per; k += gridDim.x / xcds) {
+    const uint32_t task = (first + k) * 4 + wave;
     if (task >= total) continue;
-    const int64_t e = task / a.C;
-    const int32_t c = (int32_t)(task - e * a.C);
+    const uint32_t e = task / C;
+    const int32_t c = (int32_t)(task - e * C);
     const RowTask t = rows[e];
     SupportRow sup{};
     if constexpr (SUPPORT)
