@@ -181,14 +181,50 @@ __global__ __launch_bounds__(256) void device_resid_mass(const DeviceView d, int
   if (c >= d.C) return;
   int64_t qrow; int32_t n;
   if (!device_session(d, b, &qrow, &n, false)) return;
-  const ProbWeights<PF16, ALIGNED, true> wf{static_cast<const char*>(d.p_rows) + (int64_t)b * d.V * (PF16 ? 2 : 4),
-                                            d.draft_probs + qrow * (int64_t)d.V, d.V};
-  const int64_t g0 = (int64_t)c * kChunkVecs + lane;
+  const char* pp = static_cast<const char*>(d.p_rows) + (int64_t)b * d.V * (PF16 ? 2 : 4);
+  const float* qp = d.draft_probs + qrow * (int64_t)d.V;
   float acc = 0.f;
+  if constexpr (ALIGNED) {
+    // Lane l takes entries [4l, 4l+4) of every 256-entry half-block: one 8-byte (fp16) or 16-byte
+    // (fp32) load of P~ and one 16-byte load of Q, so every wave instruction reads one contiguous
+    // stretch of its row (8 entries per lane would leave the 32-byte-per-lane loads touching half
+    // of each cache line they visit).  All loads of the chunk are in flight at once.
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    constexpr int kHalves = 4096 / 256;
+    const int64_t e_chunk = (int64_t)c * 4096 + lane * 4;
+    f32x4 p[kHalves], q[kHalves];
 #pragma unroll
-  for (int k = 0; k < kUnroll; ++k) {
-    float w[8];
-    acc += wf.group(g0 + k * kWave, w);
+    for (int h = 0; h < kHalves; ++h) {
+      const int64_t e0 = e_chunk + h * 256;
+      const bool inside = e0 < d.V;                       // V is a multiple of 8: inside means entirely inside
+      const int64_t ec = inside ? e0 : (int64_t)d.V - 4;
+      if constexpr (PF16) {
+        const u32x2 raw = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(pp + ec * 2));
+        p[h] = (f32x4){(float)__builtin_bit_cast(_Float16, (uint16_t)(raw[0] & 0xFFFFu)),
+                       (float)__builtin_bit_cast(_Float16, (uint16_t)(raw[0] >> 16)),
+                       (float)__builtin_bit_cast(_Float16, (uint16_t)(raw[1] & 0xFFFFu)),
+                       (float)__builtin_bit_cast(_Float16, (uint16_t)(raw[1] >> 16))};
+      } else {
+        p[h] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(pp + ec * 4));
+      }
+      q[h] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(qp + ec));
+      if (!inside) {
+        p[h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        q[h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+    }
+#pragma unroll
+    for (int h = 0; h < kHalves; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc += fmaxf(0.f, p[h][i] - q[h][i]);
+  } else {
+    const ProbWeights<PF16, ALIGNED, true> wf{pp, qp, d.V};
+    const int64_t g0 = (int64_t)c * kChunkVecs + lane;
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+      float w[8];
+      acc += wf.group(g0 + k * kWave, w);
+    }
   }
   acc = wave_sum(acc);
   if (lane == 0) d.resid_mass[(int64_t)b * d.C + c] = acc;
