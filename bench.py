@@ -574,6 +574,20 @@ def main():
         result["roofline"]["measured_read_ceiling_probe"] = {k: ceil[k] for k in ("loads_per_lane", "waves_per_cu")}
         result["roofline"]["frac_of_measured_read_ceiling"] = achieved / ceil["GBps"]
         result["roofline"]["probe_sweep_GBps"] = ceil["all_GBps"]
+        # the second streaming kernel against the same peak, and against what the probe reaches
+        # over as many bytes as one of its launches moves (a launch that short pays its ramp and
+        # tail: the ceiling of a 1 GB launch is below that of a 5 GB one)
+        rm = kernels.get("resid_mass")
+        if rm and ab["residual"] >= (64 << 20) and not args.early_exit:
+            rate = ab["residual"] / (rm["avg_us"] * 1e-6) / 1e9
+            short = read_ceiling(ctx, D, torch, lg.data_ptr(), min(nbytes, int(ab["residual"])))
+            result["resid_mass_roofline"] = {
+                "bound": "hbm", "achieved": rate, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": rate / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": int(ab["residual"]),
+                "avg_launch_us": rm["avg_us"],
+                "measured_read_ceiling_same_bytes_GBps": short["GBps"],
+                "measured_read_ceiling_probe": {k: short[k] for k in ("loads_per_lane", "waves_per_cu")},
+                "frac_of_measured_read_ceiling": rate / short["GBps"]}
     # spread of one step: per-step HIP events in a region of their own
     def one_step(step):
         batch.step = step

@@ -38,6 +38,9 @@ def test_headline_line_of_a_mid_sized_workload():
     assert 0.3 < roof["frac"] < 1.0                                  # a statistics kernel that streams
     assert roof["avg_launch_us"] * 1e-3 < r["ms_per_step"]           # the dominant kernel fits inside the step
     assert roof["frac_of_measured_read_ceiling"] <= 1.0              # the probe sweep is a ceiling
+    rm = r["resid_mass_roofline"]                                    # cfg2: 242 rejected sessions
+    assert rm["algorithmic_bytes_per_launch"] == r["config"]["rejected_sessions"] * 128256 * 6
+    assert 0.2 < rm["frac"] < 1.0 and rm["frac_of_measured_read_ceiling"] <= 1.0
     ev = r["step_events"]
     assert ev["min_ms"] <= ev["median_ms"] <= ev["max_ms"]
     cpu = r["cpu_baseline"]
