@@ -27,13 +27,33 @@ static_assert(kMaxSupport == DSSD_MAX_SUPPORT, "header and kernels must agree on
 static __device__ __align__(256) unsigned char scratch[DSSD_STATIC_SCRATCH_BYTES];
 
 namespace {
+// What the launches need to know about a device; the defaults are the MI355X's.
+struct DeviceFacts {
+  int32_t xcds = 8;
+  int32_t cus = 256;
+  int64_t lds_per_cu = 160 << 10;
+};
+DeviceFacts read_device_facts(int device) {
+  DeviceFacts f;
+  int attr = 0;
+  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeNumberOfXccs, device) == hipSuccess && attr >= 1) f.xcds = attr;
+  else (void)hipGetLastError();
+  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && attr >= 1) f.cus = attr;
+  else (void)hipGetLastError();
+  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device) == hipSuccess &&
+      attr >= (64 << 10))
+    f.lds_per_cu = attr;
+  else (void)hipGetLastError();
+  return f;
+}
+
 constexpr int kMaxDevices = 64;
 std::mutex scratch_lock;
-void* scratch_ptr[kMaxDevices] = {};      // device address of device d's copy of `scratch`, once resolved
-int32_t scratch_xcds[kMaxDevices] = {};   // and that device's XCD count
+void* scratch_ptr[kMaxDevices] = {};       // device address of device d's copy of `scratch`, once resolved
+DeviceFacts scratch_facts[kMaxDevices];    // and that device's facts
 
 // Address of the CURRENT device's copy of `scratch`, resolved on the first request per device.
-dssd_status current_scratch(void** ptr, int32_t* xcds) {
+dssd_status current_scratch(void** ptr, DeviceFacts* facts) {
   int device = -1;
   if (hipGetDevice(&device) != hipSuccess) { (void)hipGetLastError(); return DSSD_EHIP; }
   if (device < 0 || device >= kMaxDevices) return DSSD_EUNSUPPORTED;
@@ -41,16 +61,11 @@ dssd_status current_scratch(void** ptr, int32_t* xcds) {
   if (!scratch_ptr[device]) {
     void* p = nullptr;
     if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return DSSD_EHIP; }
-    int attr = 0;
-    if (hipDeviceGetAttribute(&attr, hipDeviceAttributeNumberOfXccs, device) != hipSuccess || attr < 1) {
-      (void)hipGetLastError();
-      attr = 8;
-    }
-    scratch_xcds[device] = attr;
+    scratch_facts[device] = read_device_facts(device);
     scratch_ptr[device] = p;
   }
   *ptr = scratch_ptr[device];
-  *xcds = scratch_xcds[device];
+  *facts = scratch_facts[device];
   return DSSD_OK;
 }
 }  // namespace
@@ -148,13 +163,8 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   dssd_ctx* c = new (std::nothrow) dssd_ctx;
   if (!c) return DSSD_ENOMEM;
   c->device = device;
-  int attr = 0;
-  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeNumberOfXccs, device) == hipSuccess && attr >= 1) c->xcds = attr;
-  else (void)hipGetLastError();
-  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && attr >= 1) c->cus = attr;
-  else (void)hipGetLastError();
-  if (hipDeviceGetAttribute(&attr, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device) == hipSuccess && attr >= (64 << 10)) c->lds_per_cu = attr;
-  else (void)hipGetLastError();
+  const DeviceFacts facts = read_device_facts(device);
+  c->xcds = facts.xcds; c->cus = facts.cus; c->lds_per_cu = facts.lds_per_cu;
   c->max_rows = max_rows;
   c->max_V = max_V;
   c->max_C = chunks_per_row(max_V, DSSD_F32);  // fp32 chunks hold fewer elements: the larger count
@@ -189,8 +199,8 @@ extern "C" dssd_status dssd_create(dssd_ctx** out, int device, int64_t max_rows,
   }
   {   // the static scratch of this device is resolved here too, so that a later dssd_step_static
       // on it has nothing left to set up (a failure only matters to that call, which repeats it)
-    void* p; int32_t x;
-    (void)current_scratch(&p, &x);
+    void* p; DeviceFacts f;
+    (void)current_scratch(&p, &f);
   }
   *out = c;
   return DSSD_OK;
@@ -585,12 +595,12 @@ extern "C" dssd_status dssd_step_static(const dssd_batch* b, dssd_out* o, void* 
   const size_t end = at_arrive + align256(2 * B * sizeof(int32_t));
   if (end > DSSD_STATIC_SCRATCH_BYTES) return DSSD_ENOMEM;
   void* base = nullptr;
-  int32_t xcds = 8;
-  const dssd_status got = current_scratch(&base, &xcds);
+  DeviceFacts facts;
+  const dssd_status got = current_scratch(&base, &facts);
   if (got != DSSD_OK) return got;
   char* p = static_cast<char*>(base);
   dssd_ctx c;   // a view of the scratch with the library's default settings; owns nothing
-  c.xcds = xcds;
+  c.xcds = facts.xcds; c.cus = facts.cus; c.lds_per_cu = facts.lds_per_cu;
   c.max_rows = (int64_t)rows; c.max_V = b->V; c.max_C = C;
   c.chunk_stats = reinterpret_cast<float2*>(p + at_chunk_stats);
   c.row_tab = reinterpret_cast<float2*>(p + at_row_tab);
