@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "a60b9474e423c42d567906eaa502e796e546ce8cfb6881fdc95f5e1c74e8534f",
-        "bytes_per_launch": int((2426293.2 * 2.0 + 4776.7 * 1.0) * 1024),
+        "sources_sha256": "92ad23e6ae7daf236b3ea0a8d71e36313b759f0e131080bf6d3e5fe6d577d845",
+        "bytes_per_launch": int((2426293.0 * 2.0 + 4776.7 * 1.0) * 1024),
         "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }
@@ -46,13 +46,13 @@ def kernel_sources_digest():
     return h.hexdigest()
 
 
-def algorithmic_bytes(inputs, rejected, C_bonus_fraction):
+def algorithmic_bytes(inputs, n_rej, C_bonus_fraction):
     """Bytes the method must move in one step: every logits row once; for each rejected
     session its P row again plus its Q row; for each accepted session one chunk of the bonus
-    row; the per-position gathers; the result records."""
+    row; the per-position gathers; the result records.  n_rej: rejected sessions per step (a
+    mean over the steps measured, so it need not be whole)."""
     V, B, R_L, R_Q = inputs["V"], inputs["B"], inputs["R_L"], inputs["R_Q"]
     s_L = inputs["logits"].element_size()
-    n_rej = int(rejected.sum())
     stats = R_L * V * s_L
     resid = n_rej * V * (s_L + 4)
     bonus = (B - n_rej) * V * s_L * C_bonus_fraction
@@ -337,7 +337,7 @@ def config_summary(D, torch, synth, idx, seed, steps, warmup):
     rejected = outs["rejected"].cpu().numpy()
     s_L = inputs["logits"].element_size()
     C = -(-w.V // (4096 if s_L == 2 else 2048))
-    ab = algorithmic_bytes(inputs, rejected, 1.0 / C)
+    ab = algorithmic_bytes(inputs, int(rejected.sum()), 1.0 / C)   # the last step's count stands for all
     k1_us = 1e3 * k1_ms / max(k1_n, 1)
     res.update({
         "three_calls": {"ms_per_step": mean3, "positions_per_sec": inputs["R_Q"] / (mean3 * 1e-3), "events": ev3},
@@ -493,20 +493,33 @@ def main():
     assert dom_n == args.steps or (args.early_exit and dom_n % args.steps == 0)
     dom_per_step = dom_n // args.steps     # early exit: the statistics kernel runs once per round
 
+    # How many sessions a step rejects depends on the step's random numbers: the timed steps are
+    # run once more, untimed, to count them (the byte figures below use the mean).
+    rej_total = torch.zeros((), dtype=torch.int64, device=dev)
+    for k in range(args.steps):
+        batch.step = args.warmup + k
+        step_fn(batch, out)
+        rej_total += outs["rejected"].sum()
+    mean_rejected = float(rej_total.item()) / max(args.steps, 1)
+
     # Per-kernel breakdown from a second, separate region with every kernel bracketed.
     D.dssd_profile_reset(ctx.handle)
     D.dssd_profile_enable(ctx.handle, True)
-    for k in range(min(args.steps, 50)):
+    rej_total.zero_()
+    n_breakdown = min(args.steps, 50)
+    for k in range(n_breakdown):
         batch.step = args.warmup + args.steps + k
         step_fn(batch, out)
+        rej_total += outs["rejected"].sum()
     torch.cuda.synchronize()
     D.dssd_profile_enable(ctx.handle, False)
     kernels = {k: v for k, v in read_kernels().items() if v["launches"]}
-    rejected = outs["rejected"].cpu().numpy()
+    mean_rejected_breakdown = float(rej_total.item()) / max(n_breakdown, 1)
+    rejected = outs["rejected"].cpu().numpy()   # the last step's flags, for the paper's link model
     s_L = inputs["logits"].element_size()
     chunk_elems = 4096 if s_L == 2 else 2048
     C = -(-w.V // chunk_elems)
-    ab = algorithmic_bytes(inputs, rejected, 1.0 / C)
+    ab = algorithmic_bytes(inputs, mean_rejected, 1.0 / C)
     if flags & D.FLAG_SPARSE_SUPPORT:   # the samplers touch a few dozen entries per session, not rows
         ab["total"] -= ab["residual"] + ab["bonus"]
         ab["residual"] = ab["bonus"] = 0
@@ -542,7 +555,7 @@ def main():
                    "input_copies_rotated": max(args.rotate, 1), "top_k": args.top_k, "sparse_support": bool(flags & D.FLAG_SPARSE_SUPPORT),
                    "early_exit": bool(flags & D.FLAG_EARLY_EXIT),
                    "logits_rows": inputs["R_L"], "draft_positions": inputs["R_Q"],
-                   "rejected_sessions": int(rejected.sum())},
+                   "rejected_sessions": mean_rejected},
         "vocab_rows_per_sec": inputs["R_L"] * args.steps / elapsed,
         "step_algorithmic_GBps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -578,12 +591,14 @@ def main():
         # over as many bytes as one of its launches moves (a launch that short pays its ramp and
         # tail: the ceiling of a 1 GB launch is below that of a 5 GB one)
         rm = kernels.get("resid_mass")
-        if rm and ab["residual"] >= (64 << 20) and not args.early_exit:
-            rate = ab["residual"] / (rm["avg_us"] * 1e-6) / 1e9
-            short = read_ceiling(ctx, D, torch, lg.data_ptr(), min(nbytes, int(ab["residual"])))
+        rm_bytes = mean_rejected_breakdown * w.V * (s_L + 4)   # over the launches that were bracketed
+        if rm and rm_bytes >= (64 << 20) and not args.early_exit:
+            rate = rm_bytes / (rm["avg_us"] * 1e-6) / 1e9
+            short = read_ceiling(ctx, D, torch, lg.data_ptr(), min(nbytes, int(rm_bytes)))
             result["resid_mass_roofline"] = {
                 "bound": "hbm", "achieved": rate, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": rate / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": int(ab["residual"]),
+                "frac": rate / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": rm_bytes,
+                "rejected_sessions_per_launch": mean_rejected_breakdown,
                 "avg_launch_us": rm["avg_us"],
                 "measured_read_ceiling_same_bytes_GBps": short["GBps"],
                 "measured_read_ceiling_probe": {k: short[k] for k in ("loads_per_lane", "waves_per_cu")},

@@ -4,7 +4,6 @@ import os
 import subprocess
 import sys
 
-import numpy as np
 import torch
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -22,13 +21,14 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_algorithmic_bytes_of_a_step():
     # 3 sessions, gamma = 2, V = 1000, bf16 logits: 9 logits rows, 6 draft rows
     inputs = dict(V=1000, B=3, R_L=9, R_Q=6, logits=torch.zeros((9, 1000), dtype=torch.bfloat16))
-    rejected = np.array([1, 0, 1])
-    ab = bench.algorithmic_bytes(inputs, rejected, C_bonus_fraction=0.25)
+    ab = bench.algorithmic_bytes(inputs, 2, C_bonus_fraction=0.25)      # two of the three sessions rejected
     assert ab["row_stats"] == 9 * 1000 * 2                 # every logits row once
     assert ab["residual"] == 2 * 1000 * (2 + 4)            # P row again + Q row, per rejected session
     assert ab["bonus"] == 1 * 1000 * 2 * 0.25              # one chunk of the bonus row
     assert ab["gathers"] == 6 * (4 + 4 + 2) and ab["records"] == 36
     assert ab["total"] == sum(ab[k] for k in ("row_stats", "residual", "bonus", "gathers", "records"))
+    half = bench.algorithmic_bytes(inputs, 1.5, C_bonus_fraction=0.25)  # a mean over steps need not be whole
+    assert half["residual"] == 1.5 * 1000 * 6 and half["bonus"] == 1.5 * 1000 * 2 * 0.25
 
 
 def test_traffic_figure_is_tied_to_the_kernel_sources():
