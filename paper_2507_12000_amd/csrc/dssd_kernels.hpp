@@ -354,9 +354,15 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, i
       }
     }
     if (lane == 0) {
-      Job none, job;
-      none.lrow = -1; none.M2 = 0.f; none.Z = 0.f;
+      // (records are built field by field: choosing between two whole structs made the compiler
+      // park both in scratch memory and pick one by address, at the end of a latency-bound chain)
+      Job job;
       job.lrow = lrow0 + first_reject; job.M2 = sel_st.x; job.Z = sel_st.y;
+      const auto job_if = [&](bool wanted) {
+        Job j;
+        j.lrow = wanted ? job.lrow : -1; j.M2 = wanted ? job.M2 : 0.f; j.Z = wanted ? job.Z : 0.f;
+        return j;
+      };
       if (!open) {
         if (bad) {
           a.accepted_len[b] = 0;
@@ -366,8 +372,8 @@ __device__ int32_t accept_session(const BatchView& a, int32_t b, Job* job_out, i
           a.accepted_len[b] = first_reject;
           a.rejected[b] = first_reject < g ? 1 : 0;
         }
-        a.resid_job[b] = (!bad && first_reject < g) ? job : none;
-        a.bonus_job[b] = (!bad && first_reject == g) ? job : none;
+        a.resid_job[b] = job_if(!bad && first_reject < g);
+        a.bonus_job[b] = job_if(!bad && first_reject == g);
         if (a.status) a.status[b] = bad;
       }
       sh_job = job;
