@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "92ad23e6ae7daf236b3ea0a8d71e36313b759f0e131080bf6d3e5fe6d577d845",
-        "bytes_per_launch": int((2426293.0 * 2.0 + 4776.7 * 1.0) * 1024),
+        "sources_sha256": "2ba1b3c6d7a5edc74d52d5a59a1568cb95f5530b9bb7fca95595928a4adb0523",
+        "bytes_per_launch": int((2426293.3 * 2.0 + 4776.7 * 1.0) * 1024),
         "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }
