@@ -19,6 +19,8 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+EVENT_POOL = 2048       # timing brackets the library keeps per kernel between two resets
+MAX_ROUNDS = 8          # early exit: most rounds a step can have
 
 # HBM bytes per launch of row_chunk_stats from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # what the same counters read for a plain copy of known size; profiles/step_cfg4_hbm_bytes_pmc.txt).
@@ -479,10 +481,16 @@ def main():
     # (with early exit the library may decide that the batch is too small for it and run the
     # default kernels: whichever statistics kernel was launched is the one that is reported)
     cands = [D.K_ROW_STATS_BLOCK, D.K_ROW_STATS, D.K_FUSED_STEP] if args.early_exit else [dom_id]
+    # The library holds a fixed pool of event pairs per kernel (EVENT_POOL brackets between two
+    # resets): a longer run brackets its first steps only.  Early exit launches the statistics
+    # kernel once per round, at most MAX_ROUNDS times a step.
+    bracketed = min(args.steps, EVENT_POOL // (MAX_ROUNDS if args.early_exit else 1))
     D.dssd_profile_reset(ctx.handle)
     D.dssd_profile_enable(ctx.handle, sum(1 << k for k in cands))
     t0 = time.perf_counter()
     for k in range(args.steps):
+        if k == bracketed:
+            D.dssd_profile_enable(ctx.handle, False)   # a host-side switch: nothing is synchronised
         batch.step = args.warmup + k
         step_fn(batch, out)
     torch.cuda.synchronize()
@@ -490,8 +498,8 @@ def main():
     D.dssd_profile_enable(ctx.handle, False)
     dom_id = next(k for k in cands if D.dssd_profile_read(ctx.handle, k)[1] > 0)
     dom_ms, dom_n = D.dssd_profile_read(ctx.handle, dom_id)
-    assert dom_n == args.steps or (args.early_exit and dom_n % args.steps == 0)
-    dom_per_step = dom_n // args.steps     # early exit: the statistics kernel runs once per round
+    assert dom_n == bracketed or (args.early_exit and dom_n % bracketed == 0)
+    dom_per_step = dom_n // bracketed      # early exit: the statistics kernel runs once per round
 
     # How many sessions a step rejects depends on the step's random numbers: the timed steps are
     # run once more, untimed, to count them (the byte figures below use the mean).

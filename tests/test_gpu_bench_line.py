@@ -62,6 +62,17 @@ def test_all_configs_block_and_small_modes():
         assert q["value"] > 0 and q["ms_per_step"] > 0, extra
 
 
+def test_more_steps_than_the_library_has_timing_brackets():
+    """The library keeps 2048 event pairs per kernel: a longer run brackets its first steps only
+    and still times all of them by the wall clock."""
+    r = _run("--config", "0", "--steps", "2500", "--warmup", "5", "--no-cpu-baseline", "--no-all-configs",
+             "--headline-only")
+    assert r["steps"] == 2500 and r["value"] > 0 and r["roofline"]["avg_launch_us"] > 0
+    q = _run("--config", "2", "--steps", "300", "--warmup", "5", "--no-cpu-baseline", "--no-all-configs",
+             "--early-exit", "--fused")
+    assert q["steps"] == 300 and q["value"] > 0 and q["roofline"]["avg_launch_us"] > 0
+
+
 def test_copy_probe_line():
     r = _run("--copy-probe")
     assert r["copy_probe"] and r["bytes_read_per_launch"] == 2 << 30 and r["GBps_read_plus_write"] > 1000
