@@ -66,3 +66,34 @@ def test_static_step_refuses_what_does_not_fit_or_needs_lists():
     torch.cuda.synchronize()
     assert (t["accepted_len"] == -7).all() and (t["out_token"] == -7).all()
     assert D.dssd_step_static(None, out, 0, check=False) == D.DSSD_EINVAL
+
+
+def test_static_step_inside_a_hip_graph():
+    """The callers the entry point is for include code under graph capture: the call (a fill
+    kernel for its counters, then the step's kernels; no allocation, no memset node) is recorded
+    once and replayed, with other calls on the shared array and synchronisations between the
+    replays, and every replay reproduces the eager result."""
+    w = synth.Workload("static_graph", B=24, V=4096 * 3 + 8, gamma=5, dtype="bf16", sigmas=(0.5, 1.5))
+    inputs = synth.generate(w, seed=7, device=DEV)
+    other_inputs = synth.generate(SECOND, seed=3, device=DEV)
+    stream = torch.cuda.current_stream(DEV).cuda_stream
+    eager = _outputs(lambda b, o: D.dssd_step_static(b, o, stream), inputs, 31, 2)
+    batch = D.make_batch(inputs, seed=31, step=2)
+    t, out = D.alloc_out(inputs, DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        D.dssd_step_static(batch, out, side.cuda_stream)          # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            D.dssd_step_static(batch, out, side.cuda_stream)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for v in t.values():
+            v.fill_(-3)
+        _outputs(lambda b, o: D.dssd_step_static(b, o, stream), other_inputs, 5, rep)   # re-carves the array
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in eager:
+            assert torch.equal(t[k], eager[k]), (k, rep)
