@@ -106,11 +106,34 @@ __device__ __forceinline__ float wave_scan(float x, int /*lane*/) {
 // per_vec, so the group is one 128-bit load; it is issued non-temporal (the rows are streamed
 // once and far exceed the caches) and without a branch (the address is clamped into the row,
 // the value replaced afterwards).
-template <bool BF16, bool ALIGNED>
+// INSIDE (rows that are not ALIGNED): the caller knows that the whole group lies within the row;
+// it is then one 128-bit load at the row's element alignment, which the hardware serves at any
+// alignment (a load that straddles cache lines costs a second access), instead of per_vec scalar
+// loads.
+typedef u32x4 u32x4_at2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_at4 __attribute__((aligned(4)));
+typedef f32x4 f32x4_at4 __attribute__((aligned(4)));
+template <bool BF16, bool ALIGNED, bool INSIDE = false>
 __device__ __forceinline__ void load_logits(const void* row, int64_t vec, int32_t V, float* z) {
   constexpr int E = Elems<BF16>::per_vec;
   const int64_t e0 = vec * E;
-  if constexpr (ALIGNED) {
+  if constexpr (!ALIGNED && INSIDE) {
+    u32x4 v;
+    if constexpr (BF16)
+      v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_at2*>(static_cast<const uint16_t*>(row) + e0));
+    else
+      v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_at4*>(static_cast<const float*>(row) + e0));
+    if constexpr (BF16) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        z[2 * i] = as_float(v[i] << 16);
+        z[2 * i + 1] = as_float(v[i] & 0xFFFF0000u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z[i] = as_float(v[i]);
+    }
+  } else if constexpr (ALIGNED) {
     const int64_t last = V / E - 1;
     const bool inside = vec <= last;
     const u32x4* p = reinterpret_cast<const u32x4*>(row) + (inside ? vec : last);
@@ -148,9 +171,16 @@ __device__ __forceinline__ float load_logit(const void* row, int64_t e, bool bf1
 }
 // Loads draft probabilities [e0, e0+N) of a row (N = 4 or 8, e0 a multiple of N); entries at
 // or beyond V read as 0.  ALIGNED as above: non-temporal 128-bit loads, clamped, no branch.
-template <int N, bool ALIGNED>
+template <int N, bool ALIGNED, bool INSIDE = false>
 __device__ __forceinline__ void load_probs(const float* row, int64_t e0, int32_t V, float* q) {
-  if constexpr (ALIGNED) {
+  if constexpr (!ALIGNED && INSIDE) {
+    const f32x4_at4* p = reinterpret_cast<const f32x4_at4*>(row + e0);
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) {
+      const f32x4 v = __builtin_nontemporal_load(p + i);
+      q[4 * i] = v[0]; q[4 * i + 1] = v[1]; q[4 * i + 2] = v[2]; q[4 * i + 3] = v[3];
+    }
+  } else if constexpr (ALIGNED) {
     const bool inside = e0 < V;
     const f32x4* p = reinterpret_cast<const f32x4*>(row + (inside ? e0 : (int64_t)V - N));
 #pragma unroll

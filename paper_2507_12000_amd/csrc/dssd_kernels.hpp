@@ -107,8 +107,16 @@ __device__ __forceinline__ float2 chunk_stats_of(const char* src, int32_t c, int
   constexpr int E = Elems<BF16>::per_vec;
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
   float z[kUnroll][E];
+  // Rows that are not 16-byte aligned: every chunk but a row's last lies entirely inside the row
+  // (a wave-uniform test) and is read with 128-bit loads at the row's own alignment; the last
+  // chunk takes scalar loads, which stop at the row's end.
+  if (!ALIGNED && (int64_t)(c + 1) * kChunkVecs * E <= V) {
 #pragma unroll
-  for (int k = 0; k < kUnroll; ++k) load_logits<BF16, ALIGNED>(src, v0 + k * kWave, V, z[k]);
+    for (int k = 0; k < kUnroll; ++k) load_logits<BF16, ALIGNED, true>(src, v0 + k * kWave, V, z[k]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) load_logits<BF16, ALIGNED>(src, v0 + k * kWave, V, z[k]);
+  }
   const float c1 = c1_of();
 
   float mx = neg_inf();
@@ -486,16 +494,25 @@ __device__ __forceinline__ float resid_chunk_mass(const BatchView& a, int32_t b,
     // fp32 logits are 4 per 16-byte group, like Q: already one contiguous stretch per instruction.
     // Streaming launches take two half-chunks of 4 groups each (measured faster than all 8 at
     // once there); a lone workgroup finishing a session takes all 8 (one round trip fewer).
-    // Unaligned rows take the scalar loads of load_logits.
+    // Unaligned rows: vector loads at the row's alignment inside the row, scalar loads in its last chunk.
     constexpr int G = GROUPS_IN_FLIGHT;
     const int64_t v0 = (int64_t)c * kChunkVecs + lane;
+    const bool inside = !ALIGNED && (int64_t)(c + 1) * kChunkVecs * E <= a.V;   // wave-uniform, as in chunk_stats_of
 #pragma unroll
     for (int k0 = 0; k0 < kUnroll; k0 += G) {
       float z[G][E], q[G][E];
+      if (inside) {
 #pragma unroll
-      for (int k = 0; k < G; ++k) {
-        load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
-        load_probs<E, ALIGNED>(qp, (v0 + (k0 + k) * kWave) * E, a.V, q[k]);
+        for (int k = 0; k < G; ++k) {
+          load_logits<BF16, ALIGNED, true>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
+          load_probs<E, ALIGNED, true>(qp, (v0 + (k0 + k) * kWave) * E, a.V, q[k]);
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+          load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
+          load_probs<E, ALIGNED>(qp, (v0 + (k0 + k) * kWave) * E, a.V, q[k]);
+        }
       }
 #pragma unroll
       for (int k = 0; k < G; ++k)

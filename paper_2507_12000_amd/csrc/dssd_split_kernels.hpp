@@ -25,44 +25,56 @@ __global__ __launch_bounds__(256) void export_p_rows(const BatchView a, int32_t 
   const char* lp = logits_row<BF16>(a, job.lrow);
   const int64_t v0 = (int64_t)c * kChunkVecs + lane;
   char* out_row = static_cast<char*>(p_rows) + (int64_t)b * a.V * (F16OUT ? 2 : 4);
+  // Rows that are not 16-byte aligned: a chunk that lies entirely inside the row (wave-uniform)
+  // is read and written with vector accesses at the rows' own alignment, the last chunk scalar.
+  const bool inside = !ALIGNED && (int64_t)(c + 1) * kChunkVecs * E <= a.V;
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  typedef u32x2 u32x2_at2 __attribute__((aligned(2)));
+  using Store16 = typename std::conditional<ALIGNED, u32x4, u32x4_at2>::type;
+  using Store8 = typename std::conditional<ALIGNED, u32x2, u32x2_at2>::type;
+  using StoreF4 = typename std::conditional<ALIGNED, f32x4, f32x4_at4>::type;
 #pragma unroll
   for (int k0 = 0; k0 < kUnroll; k0 += 4) {
     float z[4][E];
+    if (inside) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
+      for (int k = 0; k < 4; ++k) load_logits<BF16, ALIGNED, true>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) load_logits<BF16, ALIGNED>(lp, v0 + (k0 + k) * kWave, a.V, z[k]);
+    }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int64_t e0 = (v0 + (k0 + k) * kWave) * E;
       float p[E];
 #pragma unroll
       for (int e = 0; e < E; ++e) p[e] = fast_exp2(fmaf(z[k][e], c1, -job.M2)) * invZ;
-      if constexpr (ALIGNED) {
-        if (e0 < a.V) {   // V is a multiple of E: the group is entirely inside the row
-          if constexpr (F16OUT) {
-            uint32_t packed[E / 2];
+      // aligned rows: V is a multiple of E, so a group that starts inside the row lies inside it
+      const bool whole = ALIGNED ? e0 < a.V : inside;
+      if (whole) {
+        if constexpr (F16OUT) {
+          uint32_t packed[E / 2];
 #pragma unroll
-            for (int e = 0; e < E; e += 2) {
-              const _Float16 lo = (_Float16)p[e], hi = (_Float16)p[e + 1];
-              packed[e / 2] = (uint32_t)__builtin_bit_cast(uint16_t, lo) |
-                              ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
-            }
-            if constexpr (E == 8) {
-              const u32x4 v = {packed[0], packed[1], packed[2], packed[3]};
-              __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out_row + e0 * 2));
-            } else {
-              typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-              const u32x2 v = {packed[0], packed[1]};
-              __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(out_row + e0 * 2));
-            }
+          for (int e = 0; e < E; e += 2) {
+            const _Float16 lo = (_Float16)p[e], hi = (_Float16)p[e + 1];
+            packed[e / 2] = (uint32_t)__builtin_bit_cast(uint16_t, lo) |
+                            ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+          }
+          if constexpr (E == 8) {
+            const u32x4 v = {packed[0], packed[1], packed[2], packed[3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<Store16*>(out_row + e0 * 2));
           } else {
+            const u32x2 v = {packed[0], packed[1]};
+            __builtin_nontemporal_store(v, reinterpret_cast<Store8*>(out_row + e0 * 2));
+          }
+        } else {
 #pragma unroll
-            for (int i = 0; i < E / 4; ++i) {
-              const f32x4 v = {p[4 * i], p[4 * i + 1], p[4 * i + 2], p[4 * i + 3]};
-              __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out_row + (e0 + 4 * i) * 4));
-            }
+          for (int i = 0; i < E / 4; ++i) {
+            const f32x4 v = {p[4 * i], p[4 * i + 1], p[4 * i + 2], p[4 * i + 3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<StoreF4*>(out_row + (e0 + 4 * i) * 4));
           }
         }
-      } else {
+      } else if constexpr (!ALIGNED) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           if (e0 + e < a.V) {
@@ -94,10 +106,26 @@ struct DeviceView {
 };
 
 // Groups of 8 entries of a probability row (16 bytes of fp16, 32 bytes of fp32).
-template <bool PF16, bool ALIGNED>
+// INSIDE (rows that are not ALIGNED): the group is known to lie within the row and is read with
+// vector loads at the row's element alignment.
+template <bool PF16, bool ALIGNED, bool INSIDE = false>
 __device__ __forceinline__ void load_p8(const void* row, int64_t g, int32_t V, float* p) {
   const int64_t e0 = g * 8;
-  if constexpr (ALIGNED) {
+  if constexpr (!ALIGNED && INSIDE) {
+    if constexpr (PF16) {
+      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_at2*>(static_cast<const uint16_t*>(row) + e0));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        p[2 * i] = (float)__builtin_bit_cast(_Float16, (uint16_t)(v[i] & 0xFFFFu));
+        p[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(v[i] >> 16));
+      }
+    } else {
+      const f32x4_at4* q = reinterpret_cast<const f32x4_at4*>(static_cast<const float*>(row) + e0);
+      const f32x4 lo = __builtin_nontemporal_load(q), hi = __builtin_nontemporal_load(q + 1);
+      p[0] = lo[0]; p[1] = lo[1]; p[2] = lo[2]; p[3] = lo[3];
+      p[4] = hi[0]; p[5] = hi[1]; p[6] = hi[2]; p[7] = hi[3];
+    }
+  } else if constexpr (ALIGNED) {
     const int64_t last = V / 8 - 1;
     const bool inside = g <= last;
     const int64_t gg = inside ? g : last;
@@ -132,17 +160,17 @@ __device__ __forceinline__ void load_p8(const void* row, int64_t g, int32_t V, f
 }
 
 // w = max(0, P~ - Q) (RESID) or w = P~ (fallback when the residual has no mass).
-template <bool PF16, bool ALIGNED, bool RESID>
+template <bool PF16, bool ALIGNED, bool RESID, bool INSIDE = false>
 struct ProbWeights {
   static constexpr int E = 8;
   const void* pp; const float* qp; int32_t V;
   __device__ __forceinline__ float group(int64_t g, float* w) const {
     float p[8];
-    load_p8<PF16, ALIGNED>(pp, g, V, p);
+    load_p8<PF16, ALIGNED, INSIDE>(pp, g, V, p);
     float sum = 0.f;
     if constexpr (RESID) {
       float q[8];
-      load_probs<8, ALIGNED>(qp, g * 8, V, q);
+      load_probs<8, ALIGNED, INSIDE>(qp, g * 8, V, q);
 #pragma unroll
       for (int e = 0; e < 8; ++e) { w[e] = fmaxf(0.f, p[e] - q[e]); sum += w[e]; }
     } else {
@@ -218,12 +246,21 @@ __global__ __launch_bounds__(256) void device_resid_mass(const DeviceView d, int
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc += fmaxf(0.f, p[h][i] - q[h][i]);
   } else {
-    const ProbWeights<PF16, ALIGNED, true> wf{pp, qp, d.V};
     const int64_t g0 = (int64_t)c * kChunkVecs + lane;
+    if ((int64_t)(c + 1) * 4096 <= d.V) {   // wave-uniform: the chunk lies inside the row
+      const ProbWeights<PF16, ALIGNED, true, true> wf{pp, qp, d.V};
 #pragma unroll
-    for (int k = 0; k < kUnroll; ++k) {
-      float w[8];
-      acc += wf.group(g0 + k * kWave, w);
+      for (int k = 0; k < kUnroll; ++k) {
+        float w[8];
+        acc += wf.group(g0 + k * kWave, w);
+      }
+    } else {
+      const ProbWeights<PF16, ALIGNED, true> wf{pp, qp, d.V};
+#pragma unroll
+      for (int k = 0; k < kUnroll; ++k) {
+        float w[8];
+        acc += wf.group(g0 + k * kWave, w);
+      }
     }
   }
   acc = wave_sum(acc);

@@ -50,9 +50,14 @@ SMALL = [
     # several chunks plus a ragged tail, aligned rows
     synth.Workload("f32_aligned_tail", B=9, V=10000, gamma=3, dtype="f32"),
     synth.Workload("bf16_aligned_tail", B=9, V=4096 * 2 + 8, gamma=5, dtype="bf16", sigmas=(1.0,)),
-    # rows that are not 16-byte aligned: scalar loads
+    # rows that are not 16-byte aligned: 128-bit loads at the row's own alignment for the chunks
+    # inside a row, scalar loads for its last chunk
     synth.Workload("f32_unaligned", B=7, V=9999, gamma=2, dtype="f32"),
     synth.Workload("bf16_unaligned", B=7, V=12345, gamma=4, dtype="bf16"),
+    # odd vocabularies of real tokenizers (rows start at every 2- or 4-byte phase of a 16-byte line)
+    synth.Workload("f32_V50257", B=6, V=50257, gamma=3, dtype="f32", sigmas=(1.0,)),
+    synth.Workload("bf16_V100277", B=5, V=100277, gamma=2, dtype="bf16", sigmas=(0.5, 1.5), temperature_range=(0.7, 1.3)),
+    synth.Workload("bf16_V250002", B=3, V=250002, gamma=2, dtype="bf16", sigmas=(1.0,)),
     # one chunk, smaller than a wave's share
     synth.Workload("f32_tiny_V", B=5, V=37, gamma=2, dtype="f32", zipf_s=0.5),
     synth.Workload("bf16_V1", B=3, V=1, gamma=2, dtype="bf16"),
@@ -310,7 +315,7 @@ def test_extreme_shapes(ctx, w):
 HUGE_V = [
     # a million-entry vocabulary in fp32: 513 chunks per row (nine batches of 64 in every merge and scan)
     synth.Workload("f32_V1048584", B=2, V=(1 << 20) + 8, gamma=1, dtype="f32", sigmas=(1.0,)),
-    # two million entries in bf16, unaligned rows: the scalar-load instantiation over 513 chunks
+    # two million entries in bf16, unaligned rows: the instantiation for such rows over 513 chunks
     synth.Workload("bf16_V2097155", B=2, V=(1 << 21) + 3, gamma=2, dtype="bf16", sigmas=(2.0,)),
 ]
 
@@ -330,8 +335,9 @@ def test_vocabularies_far_beyond_any_model(w):
         big.close()
 
 
-def test_misaligned_base_pointers_take_the_scalar_path(ctx):
-    """V is a multiple of 8 but the buffers start 4 bytes into a 16-byte line."""
+def test_misaligned_base_pointers(ctx):
+    """V is a multiple of 8 but the buffers start 4 bytes into a 16-byte line: the kernels for
+    unaligned rows run, and give what the aligned ones give."""
     w = synth.Workload("shifted", B=6, V=8192 + 64, gamma=3, dtype="f32", sigmas=(1.0,))
     inputs = synth.generate(w, seed=8, device=DEV)
     lg = torch.empty(inputs["logits"].numel() + 1, device=DEV, dtype=torch.float32)[1:].view_as(inputs["logits"])
