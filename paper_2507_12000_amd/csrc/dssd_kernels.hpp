@@ -405,16 +405,16 @@ __global__ __launch_bounds__(256) void accept_scan(const BatchView a) {
 // see bit-identical values: w = max(0, 2^(z*c1 - M2)*invZ - q) (residual, Algorithm 2
 // "Resample") or w = 2^(z*c1 - M2) (bonus draw from P).
 // ---------------------------------------------------------------------------------------
-template <bool BF16, bool ALIGNED, bool RESID>
+template <bool BF16, bool ALIGNED, bool RESID, bool INSIDE = false>
 __device__ __forceinline__ float group_weights(const char* lrow, const float* qrow, int64_t vec, int32_t V,
                                                float c1, float M2, float invZ, float* w) {
   constexpr int E = Elems<BF16>::per_vec;
   float z[E];
-  load_logits<BF16, ALIGNED>(lrow, vec, V, z);
+  load_logits<BF16, ALIGNED, INSIDE>(lrow, vec, V, z);
   float sum = 0.f;
   if constexpr (RESID) {
     float q[E];
-    load_probs<E, ALIGNED>(qrow, vec * E, V, q);
+    load_probs<E, ALIGNED, INSIDE>(qrow, vec * E, V, q);
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       w[e] = fmaxf(0.f, fmaf(fast_exp2(fmaf(z[e], c1, -M2)), invZ, -q[e]));
@@ -430,12 +430,18 @@ __device__ __forceinline__ float group_weights(const char* lrow, const float* qr
   return sum;
 }
 
-template <bool BF16, bool ALIGNED, bool RESID>
+// INSIDE: every group asked for lies within the row (see load_logits); inside() is the same
+// functor with that promise made.
+template <bool BF16, bool ALIGNED, bool RESID, bool INSIDE = false>
 struct LogitWeights {
   static constexpr int E = Elems<BF16>::per_vec;
+  static constexpr bool kAligned = ALIGNED;
   const char* lp; const float* qp; int32_t V; float c1, M2, invZ;
   __device__ __forceinline__ float group(int64_t vec, float* w) const {
-    return group_weights<BF16, ALIGNED, RESID>(lp, qp, vec, V, c1, M2, invZ, w);
+    return group_weights<BF16, ALIGNED, RESID, INSIDE>(lp, qp, vec, V, c1, M2, invZ, w);
+  }
+  __device__ __forceinline__ LogitWeights<BF16, ALIGNED, RESID, true> inside() const {
+    return {lp, qp, V, c1, M2, invZ};
   }
 };
 
@@ -625,6 +631,16 @@ __device__ __forceinline__ int32_t pick_in_chunk(const W& wf, int32_t c, float t
   return __shfl(token, lsel, kWave);
 }
 
+// pick_in_chunk for a chunk of any row: on rows that are not 16-byte aligned, a chunk that lies
+// entirely inside its row (wave-uniform) is read with vector loads at the row's alignment.
+template <typename W>
+__device__ __forceinline__ int32_t pick_in_chunk_of_row(const W& wf, int32_t c, float target, int lane) {
+  if constexpr (!W::kAligned) {
+    if ((int64_t)(c + 1) * kChunkVecs * W::E <= wf.V) return pick_in_chunk(wf.inside(), c, target, lane);
+  }
+  return pick_in_chunk(wf, c, target, lane);
+}
+
 // Scans per-chunk masses (lane = chunk, batches of 64) and returns the chunk that holds
 // r * total; *target_in_chunk is what is left of r * total once the chunks before it are
 // taken away.  mass(c) must be a pure function of c.  Returns -1 when total is not positive.
@@ -698,12 +714,12 @@ __device__ void pick_for_session(const BatchView& a, int32_t b, const Job& job, 
     const float* rm = a.resid_mass + (int64_t)b * a.C;
     const int32_t c = pick_chunk([&](int32_t cc) { return lds_mass ? lds_mass[cc] : observe(rm + cc); }, a.C, r,
                                  lane, &target, &total);
-    if (c >= 0) token = pick_in_chunk(LogitWeights<BF16, ALIGNED, true>{lp, qp, a.V, c1, st.x, invZ}, c, target, lane);
+    if (c >= 0) token = pick_in_chunk_of_row(LogitWeights<BF16, ALIGNED, true>{lp, qp, a.V, c1, st.x, invZ}, c, target, lane);
     if (token < 0) from_p = true;   // residual mass rounded to zero: draw from P_n instead
   }
   if (from_p) {
     const int32_t c = pick_chunk(p_mass, a.C, r, lane, &target, &total);
-    if (c >= 0) token = pick_in_chunk(LogitWeights<BF16, ALIGNED, false>{lp, nullptr, a.V, c1, st.x, invZ}, c, target, lane);
+    if (c >= 0) token = pick_in_chunk_of_row(LogitWeights<BF16, ALIGNED, false>{lp, nullptr, a.V, c1, st.x, invZ}, c, target, lane);
   }
   if (lane == 0) {
     a.out_token[b] = token;

@@ -163,7 +163,9 @@ __device__ __forceinline__ void load_p8(const void* row, int64_t g, int32_t V, f
 template <bool PF16, bool ALIGNED, bool RESID, bool INSIDE = false>
 struct ProbWeights {
   static constexpr int E = 8;
+  static constexpr bool kAligned = ALIGNED;
   const void* pp; const float* qp; int32_t V;
+  __device__ __forceinline__ ProbWeights<PF16, ALIGNED, RESID, true> inside() const { return {pp, qp, V}; }
   __device__ __forceinline__ float group(int64_t g, float* w) const {
     float p[8];
     load_p8<PF16, ALIGNED, INSIDE>(pp, g, V, p);
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(256) void device_pick(const DeviceView d) {
   float target = 0.f, total = 0.f;
   int32_t token = -1;
   int32_t c = pick_chunk([&](int32_t cc) { return rm[cc]; }, d.C, r, lane, &target, &total);
-  if (c >= 0) token = pick_in_chunk(ProbWeights<PF16, ALIGNED, true>{pp, qp, d.V}, c, target, lane);
+  if (c >= 0) token = pick_in_chunk_of_row(ProbWeights<PF16, ALIGNED, true>{pp, qp, d.V}, c, target, lane);
   bool from_p = false;
   if (token < 0) {
     // No residual mass (P~ <= Q everywhere after rounding): draw from the received P~ itself.
@@ -302,7 +304,7 @@ __global__ __launch_bounds__(256) void device_pick(const DeviceView d) {
     }
     __threadfence();   // lane 0's stores are visible to the other lanes' loads (and stale cached lines dropped)
     c = pick_chunk([&](int32_t cc) { return rm[cc]; }, d.C, r, lane, &target, &total);
-    if (c >= 0) token = pick_in_chunk(wf, c, target, lane);
+    if (c >= 0) token = pick_in_chunk_of_row(wf, c, target, lane);
   }
   if (lane == 0) {
     d.out_token[b] = token;
