@@ -29,8 +29,8 @@ MAX_ROUNDS = 8          # early exit: most rounds a step can have
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "2ba1b3c6d7a5edc74d52d5a59a1568cb95f5530b9bb7fca95595928a4adb0523",
-        "bytes_per_launch": int((2426293.3 * 2.0 + 4776.7 * 1.0) * 1024),
+        "sources_sha256": "f9d6e2304fadab0e8477326020800201b2f99350da86a47f63380b5dca0b91f2",
+        "bytes_per_launch": int((2426293.0 * 2.0 + 4776.7 * 1.0) * 1024),
         "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }
