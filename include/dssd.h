@@ -248,9 +248,8 @@ const char *dssd_status_str(dssd_status s);
  * P_i = softmax of the k listed logits times 1/T, accept iff r*q < p with p, q = 0 for a token
  * outside the respective list, redraw from norm(max(0, P_n - Q_n)) (its support lies inside the
  * target's list) or bonus token from P_gamma, both by inverse CDF in vocabulary order, the same
- * Philox blocks.  One launch; rows after a session's first rejection are not used (at most one is
- * fetched ahead), and their
- * row_stats / p_tok / q_tok entries are NaN.  Ids within one list must be distinct; -1 marks an
+ * Philox blocks.  One launch; rows after a session's first rejection are not used (at most four
+ * are fetched ahead), and their row_stats / p_tok / q_tok entries are NaN.  Ids within one list must be distinct; -1 marks an
  * unused entry; the lists need not be sorted.  Layout of sessions, rows and outputs as in
  * dssd_batch / dssd_out.  All pointers are device pointers, 4-byte aligned. */
 typedef struct {

@@ -628,7 +628,7 @@ __device__ __forceinline__ int32_t pick_in_chunk(const W& wf, int32_t c, float t
     }
     token = (int32_t)(vec * E + esel);
   }
-  return __shfl(token, lsel, kWave);
+  return __builtin_amdgcn_readlane(token, lsel);   // lsel is wave-uniform
 }
 
 // pick_in_chunk for a chunk of any row: on rows that are not 16-byte aligned, a chunk that lies
@@ -769,7 +769,7 @@ __device__ __forceinline__ int32_t draw_from_ranked(float w_ranked, int32_t idx_
   const uint64_t weighty = __ballot(w_ranked > 0.f);
   const uint64_t over = __ballot(scan > t && w_ranked > 0.f);
   const int sel = over ? __ffsll((long long)over) - 1 : 63 - __clzll((long long)weighty);
-  return __shfl(idx_ranked, sel, kWave);
+  return __builtin_amdgcn_readlane(idx_ranked, sel);   // sel is wave-uniform
 }
 
 template <bool BF16, bool RESID>
@@ -804,7 +804,7 @@ __global__ __launch_bounds__(256) void pick_sparse(const BatchView a) {
   // lanes carry the largest index and rank after every live entry, among themselves by lane)
   int32_t rank = 0;
   for (int32_t m = 0; m < kWave; ++m) {
-    const int32_t im = __shfl(idx, m, kWave);
+    const int32_t im = __builtin_amdgcn_readlane(idx, m);
     rank += (im < idx || (im == idx && m < lane)) ? 1 : 0;
   }
   const int32_t idx_r = __builtin_amdgcn_ds_permute(rank * 4, idx);

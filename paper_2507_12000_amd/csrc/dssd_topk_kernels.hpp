@@ -9,7 +9,7 @@
 //   elsewhere; inverse CDF in vocabulary order, as everywhere in this library;
 //   bonus token from P_gamma if every draft was accepted.
 // One wave per session, lane = list entry, the whole step in one launch; a session's rows are
-// read only as far as its first rejection (plus one row fetched ahead).
+// read only as far as its first rejection (plus up to four rows fetched ahead).
 #pragma once
 #include "dssd_kernels.hpp"
 
@@ -43,7 +43,7 @@ __device__ __forceinline__ int32_t draw_from_list(int32_t idx, float w, float r,
   const int32_t key = idx >= 0 ? idx : 0x7FFFFFFF;   // unused entries rank last
   int32_t rank = 0;
   for (int32_t m = 0; m < kWave; ++m) {
-    const int32_t km = __shfl(key, m, kWave);
+    const int32_t km = __builtin_amdgcn_readlane(key, m);
     rank += (km < key || (km == key && m < lane)) ? 1 : 0;
   }
   const int32_t idx_r = __builtin_amdgcn_ds_permute(rank * 4, idx);
@@ -70,28 +70,41 @@ __global__ __launch_bounds__(256) void topk_step(const TopkView t) {
   const bool in_list = lane < t.k;
   int32_t first_reject = g, token = -1, last = -1;
   if (!bad) {
-    // one position ahead: the lists of position i + 1 are asked for before position i is decided,
-    // so that their latency runs under the arithmetic (at most one row is fetched in vain)
+    // What position i reads: entry `lane` of the target's list of row i, the draft token and entry
+    // `lane` of the draft's list of position i.  Always the same five loads, from addresses
+    // clamped into the session (row min(i, g), position min(i, g-1), entry min(lane, k-1); a
+    // session without drafts reads its target row twice), and nothing is done with the values
+    // here: the number of loads in flight is then a constant the compiler can count on, and a
+    // wave never waits for lists it asked for ahead of time.  visit() masks what is not real.
     struct Lists { int32_t idx; float z; int32_t x, qi; float qp; };
+    const int32_t lk = min(lane, t.k - 1);
     auto fetch = [&](int32_t i) {
-      Lists L{-1, 0.f, 0, -1, 0.f};
-      if (i > g) return L;
-      const int64_t row = lrow0 + i;
-      if (in_list) { L.idx = t.p_idx[row * t.k + lane]; L.z = t.p_logit[row * t.k + lane]; }
-      if (i < g) {
-        const int64_t qrow = off0 + i;
-        L.x = t.tokens[qrow];
-        if (in_list) { L.qi = t.q_idx[qrow * t.k + lane]; L.qp = t.q_prob[qrow * t.k + lane]; }
-      }
+      Lists L;
+      const int64_t at_p = (lrow0 + min(i, g)) * t.k + lk;
+      const int64_t qrow = off0 + min(i, max(g - 1, 0));
+      const int32_t* x_at = g > 0 ? t.tokens + qrow : t.p_idx + at_p;
+      const int32_t* qi_at = g > 0 ? t.q_idx + qrow * t.k + lk : t.p_idx + at_p;
+      const float* qp_at = g > 0 ? t.q_prob + qrow * t.k + lk : t.p_logit + at_p;
+      L.idx = t.p_idx[at_p]; L.z = t.p_logit[at_p];
+      L.x = *x_at; L.qi = *qi_at; L.qp = *qp_at;
       return L;
     };
-    Lists next = fetch(0);
-    for (int32_t i = 0; i <= g; ++i) {
+    // The random blocks of 64 positions at a time, lane = position: one Philox evaluation per wave
+    // and batch instead of one per position inside the walk (ten rounds of quarter-rate multiplies
+    // are a third of a microsecond in a chain that is all latency).
+    uint32_t w_accept = 0, w_redraw = 0, w_bonus = 0;
+    const auto draw_blocks = [&](int32_t first) {
+      const Philox rnd = step_block(t.session_base + (uint32_t)b, (uint32_t)(first + lane), t.step_lo, t.step_hi,
+                                    t.step_dev, t.seed_lo, t.seed_hi);
+      w_accept = rnd.w[0]; w_redraw = rnd.w[1]; w_bonus = rnd.w[2];
+    };
+    draw_blocks(0);
+    // One position of the loop; false = the session is decided (or faulty) and the walk ends.
+    const auto visit = [&](int32_t i, const Lists& cur) -> bool {
       last = i;
-      const Lists cur = next;
-      next = fetch(i + 1);
+      if (i > 0 && (i & 63) == 0) draw_blocks(i);
       const int64_t row = lrow0 + i;
-      const int32_t idx = cur.idx;
+      const int32_t idx = in_list ? cur.idx : -1;
       const bool live = idx >= 0;
       const float z = live ? cur.z : neg_inf();
       const float M2 = wave_max(live ? z * c1 : neg_inf());
@@ -101,16 +114,14 @@ __global__ __launch_bounds__(256) void topk_step(const TopkView t) {
         t.row_stats[2 * row] = M2 * kLn2;
         t.row_stats[2 * row + 1] = Z;
       }
-      if (!(Z > 0.f) || !(Z < 3.0e38f) || !(fabsf(M2) < 3.0e38f)) { bad |= 8; break; }
+      if (!(Z > 0.f) || !(Z < 3.0e38f) || !(fabsf(M2) < 3.0e38f)) { bad |= 8; return false; }
       if (i == g) {   // every draft accepted: the bonus token, from P_gamma
-        const Philox rnd = step_block(t.session_base + (uint32_t)b, (uint32_t)i, t.step_lo, t.step_hi, t.step_dev,
-                                      t.seed_lo, t.seed_hi);
-        token = draw_from_list(idx, live ? e : 0.f, u01(rnd.w[2]), lane);
-        break;
+        token = draw_from_list(idx, live ? e : 0.f, u01((uint32_t)__builtin_amdgcn_readlane((int)w_bonus, i & 63)), lane);
+        return false;
       }
       const int64_t qrow = off0 + i;
       const int32_t x = cur.x;
-      const int32_t qi = cur.qi;
+      const int32_t qi = in_list ? cur.qi : -1;   // (i < g here: the draft's list of this position is real)
       const float qp = qi >= 0 ? cur.qp : 0.f;
       if (x < 0 || (t.V > 0 && x >= t.V)) {
         bad |= 1;
@@ -118,36 +129,50 @@ __global__ __launch_bounds__(256) void topk_step(const TopkView t) {
           if (t.p_tok) t.p_tok[qrow] = 0.f;
           if (t.q_tok) t.q_tok[qrow] = 0.f;
         }
-        break;
+        return false;
       }
       const uint64_t hit_p = __ballot(live && idx == x), hit_q = __ballot(qi == x);
-      const float p = hit_p ? __shfl(e, __ffsll((long long)hit_p) - 1, kWave) / Z : 0.f;
-      const float q = hit_q ? __shfl(qp, __ffsll((long long)hit_q) - 1, kWave) : 0.f;
-      const Philox rnd = step_block(t.session_base + (uint32_t)b, (uint32_t)i, t.step_lo, t.step_hi, t.step_dev,
-                                    t.seed_lo, t.seed_hi);
+      // (the lanes read here are wave-uniform: a register read, not a trip through the LDS crossbar)
+      const float p = hit_p ? lane_value(e, __ffsll((long long)hit_p) - 1) / Z : 0.f;
+      const float q = hit_q ? lane_value(qp, __ffsll((long long)hit_q) - 1) : 0.f;
+      const uint32_t r_accept = (uint32_t)__builtin_amdgcn_readlane((int)w_accept, i & 63);
       if (lane == 0) {
         if (t.p_tok) t.p_tok[qrow] = p;
         if (t.q_tok) t.q_tok[qrow] = q;
       }
-      if (__fmul_rn(u01(rnd.w[0]), q) < p) continue;   // accepted
+      if (__fmul_rn(u01(r_accept), q) < p) return true;   // accepted
       // rejected at i: x' ~ norm(max(0, P_i - Q_i)); q at each listed target id, 0 if the draft
       // does not list it
       first_reject = i;
       float q_here = 0.f;
       for (int32_t j = 0; j < t.k; ++j) {
-        const int32_t qj = __shfl(qi, j, kWave);
-        const float pj = __shfl(qp, j, kWave);
+        const int32_t qj = __builtin_amdgcn_readlane(qi, j);
+        const float pj = lane_value(qp, j);
         if (live && qj == idx) q_here = pj;
       }
       const float invZ = 1.f / Z;
       const float w = live ? fmaxf(0.f, fmaf(e, invZ, -q_here)) : 0.f;
-      const float r = u01(rnd.w[1]);
+      const float r = u01((uint32_t)__builtin_amdgcn_readlane((int)w_redraw, i & 63));
       token = draw_from_list(idx, w, r, lane);
       if (token < 0) {   // residual mass rounded to zero: draw from P_i instead
         bad |= 2;        // reported through status only; the session stays valid
         token = draw_from_list(idx, live ? e : 0.f, r, lane);
       }
-      break;
+      return false;
+    };
+    // Four positions ahead: the lists of positions i+1 .. i+4 are in flight while position i is
+    // decided, so a long run of accepted drafts costs arithmetic per position, not a round trip to
+    // memory (at most four rows are fetched in vain per session; a row is a few dozen bytes).
+    Lists l0 = fetch(0), l1 = fetch(1), l2 = fetch(2), l3 = fetch(3);
+    for (int32_t i = 0; i <= g; i += 4) {
+      if (!visit(i, l0)) break;
+      l0 = fetch(i + 4);
+      if (i + 1 > g || !visit(i + 1, l1)) break;
+      l1 = fetch(i + 5);
+      if (i + 2 > g || !visit(i + 2, l2)) break;
+      l2 = fetch(i + 6);
+      if (i + 3 > g || !visit(i + 3, l3)) break;
+      l3 = fetch(i + 7);
     }
   }
   const int32_t fatal = bad & ~2;

@@ -66,6 +66,10 @@ CASES = [
     synth.Workload("lists_bf16_top1", B=9, V=4099, gamma=3, dtype="bf16", sigmas=(1.0,), top_k=1),
     synth.Workload("lists_f32_ragged_top5", B=45, V=9000, gamma=0, dtype="f32", gamma_range=(0, 12),
                    sigmas=(0.2, 1.0), top_k=5, frac_q_equals_p=0.2),
+    # more positions than a wave has lanes: sessions whose draft equals the target accept all 70
+    # and draw their bonus token from the second batch of random blocks
+    synth.Workload("lists_f32_gamma70_top8", B=12, V=3000, gamma=70, dtype="f32", sigmas=(0.1,), top_k=8,
+                   frac_q_equals_p=0.5),
 ]
 
 
