@@ -317,6 +317,14 @@ static unsigned occupancy_cap_lds(const dssd_ctx* c, int wg_waves, int waves_per
   return (unsigned)std::min<int64_t>(bytes, 64 << 10);
 }
 
+// Threads of a session's workgroup in the accept kernels: four waves (each merges rows of its own)
+// while the chip can hold four waves for every session at once, fewer for larger batches, whose
+// workgroups would otherwise queue up behind each other for work a single wave does in one pass.
+static unsigned accept_threads(const dssd_ctx* c, int32_t B) {
+  const int64_t resident = (int64_t)c->cus * 32;   // waves the chip holds at eight per SIMD
+  return (unsigned)(kWave * std::min<int64_t>(4, std::max<int64_t>(1, resident / std::max(B, 1))));
+}
+
 static dssd_status launch_status(const dssd_ctx* c) {
   const bool launched = hipGetLastError() == hipSuccess;
   return launched && !c->ev_failed ? DSSD_OK : DSSD_EHIP;
@@ -416,8 +424,8 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
       // the round after next starts at begin[r + 2]: the next one takes the rows in between, or all
       const int32_t next_width = last ? 0 : (r + 2 < kEarlyExitRounds ? kEarlyExitBegin[r + 2] - end : 0x7FFFFFFF);
       with_flags([&](auto BF, auto AL, auto TB) {
-        DSSD_LAUNCH((accept_scan_block<FLAG(BF), FLAG(AL), FLAG(TB)>), b->B, s, v, open, begin, end, next_list,
-                    next_rows, next_lengths, next_width);
+        DSSD_LAUNCH_WG((accept_scan_block<FLAG(BF), FLAG(AL), FLAG(TB)>), b->B, accept_threads(c, b->B), 0, s, v, open,
+                       begin, end, next_list, next_rows, next_lengths, next_width);
       }, bf16, al, tail_bonus);
     }
     if (last) break;
@@ -453,9 +461,11 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
     Timed t(c, DSSD_K_ACCEPT, s);
     const unsigned g2 = (unsigned)b->B;   // one workgroup per session
     if (tail_bonus && !sparse)
-      with_flags([&](auto BF, auto AL) { DSSD_LAUNCH((accept_scan_bonus<FLAG(BF), FLAG(AL)>), g2, s, v); }, bf16, al);
+      with_flags([&](auto BF, auto AL) {
+        DSSD_LAUNCH_WG((accept_scan_bonus<FLAG(BF), FLAG(AL)>), g2, accept_threads(c, b->B), 0, s, v);
+      }, bf16, al);
     else
-      with_flags([&](auto BF) { DSSD_LAUNCH((accept_scan<FLAG(BF)>), g2, s, v); }, bf16);
+      with_flags([&](auto BF) { DSSD_LAUNCH_WG((accept_scan<FLAG(BF)>), g2, accept_threads(c, b->B), 0, s, v); }, bf16);
   }
   return launch_status(c);
 }
