@@ -29,8 +29,8 @@ MAX_ROUNDS = 8          # early exit: most rounds a step can have
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "bcf79877b727d47ef25891acfa752be0a214a26a4e09e646cc37d58334b676cb",
-        "bytes_per_launch": int((2426293.3 * 2.0 + 4776.7 * 1.0) * 1024),
+        "sources_sha256": "c3f9aa90b7c5c01bbe08ebd52d8caafa455ad3749d577504288d2b4ec0af1bbb",
+        "bytes_per_launch": int((2426287.4 * 2.0 + 4776.7 * 1.0) * 1024),
         "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }

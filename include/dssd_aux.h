@@ -32,8 +32,8 @@ dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
  * and loses several percent towards full occupancy, so the library caps them (by requesting LDS
  * the kernels never touch).  0 = no cap (whatever the registers allow).  Values are rounded
  * down to whole workgroups, never below two workgroups per unit.  Until this is called both are
- * 16, except that fp32 logits of 1 GiB and more per batch take their statistics at 12 (measured
- * on MI355X: 1-4 % faster there, slower on smaller batches). */
+ * 16, except that a statistics launch over 1 GiB of logits and more runs at 12 (measured on
+ * MI355X: 1-4 % faster there, slower on smaller batches). */
 dssd_status dssd_set_stream_occupancy(dssd_ctx *ctx, int32_t stats_waves_per_cu, int32_t resid_waves_per_cu);
 
 /* ---- kernel timing ---- */

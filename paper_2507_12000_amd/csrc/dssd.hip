@@ -81,9 +81,9 @@ struct dssd_ctx {
   // LDS the kernels never touch; 0 = whatever the registers allow.
   int32_t stats_waves_per_cu = 16;
   int32_t resid_waves_per_cu = 16;
-  // Until the caller sets the caps: fp32 logits of a gigabyte and more take their statistics at 12
-  // waves per unit (measured 1-4 % faster than 16 there, 2-5 % slower below 400 MB; bf16 rows
-  // gain or lose under 1 % either way and stay at 16).
+  // Until the caller sets the caps: a statistics launch over a gigabyte of logits and more runs at
+  // 12 waves per unit (measured 1-4 % faster than 16 there, for either dtype, on shapes from
+  // V = 32 000 to 256 000; 2-5 % slower below 600 MB, where 16 stays).
   bool stats_cap_auto = true;
   int64_t max_rows = 0;
   int32_t max_V = 0;
@@ -325,6 +325,11 @@ static unsigned accept_threads(const dssd_ctx* c, int32_t B) {
   return (unsigned)(kWave * std::min<int64_t>(4, std::max<int64_t>(1, resident / std::max(B, 1))));
 }
 
+// Waves per compute unit for a statistics launch that reads `bytes` of logits.
+static int32_t stats_waves_for(const dssd_ctx* c, int64_t bytes) {
+  return c->stats_cap_auto && bytes >= ((int64_t)1 << 30) ? 12 : c->stats_waves_per_cu;
+}
+
 static dssd_status launch_status(const dssd_ctx* c) {
   const bool launched = hipGetLastError() == hipSuccess;
   return launched && !c->ev_failed ? DSSD_OK : DSSD_EHIP;
@@ -402,7 +407,8 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
         const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
         with_flags([&](auto BF, auto AL, auto SP) {
           DSSD_LAUNCH_WG((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, 256,
-                         occupancy_cap_lds(c, 4, c->stats_waves_per_cu, blocks), s, v, w, c->open_count, kMaxRounds);
+                         occupancy_cap_lds(c, 4, stats_waves_for(c, (int64_t)b->B * w * b->V * (bf16 ? 2 : 4)), blocks), s,
+                         v, w, c->open_count, kMaxRounds);
         }, bf16, al, sparse);
       } else {
         // the rows listed by the accept launch before: at most every row that is left
@@ -450,8 +456,7 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
     hipLaunchKernelGGL(zero_i32, dim3((unsigned)((v.R_L + 255) / 256)), dim3(256), 0, s, v.support_count, v.R_L);
   {
     Timed t(c, DSSD_K_ROW_STATS, s);
-    int32_t waves_per_cu = c->stats_waves_per_cu;
-    if (c->stats_cap_auto && !bf16 && v.R_L * (int64_t)b->V * 4 >= ((int64_t)1 << 30)) waves_per_cu = 12;
+    const int32_t waves_per_cu = stats_waves_for(c, v.R_L * (int64_t)b->V * (bf16 ? 2 : 4));
     with_flags([&](auto BF, auto AL, auto SP) {
       DSSD_LAUNCH_WG((row_chunk_stats<FLAG(BF), FLAG(AL), FLAG(SP)>), grid, kStatsWaves * kWave,
                      occupancy_cap_lds(c, kStatsWaves, waves_per_cu, grid), s, v);
