@@ -31,9 +31,10 @@ dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
  * resident: read throughput on this chip peaks at a moderate number of bytes in flight per unit
  * and loses several percent towards full occupancy, so the library caps them (by requesting LDS
  * the kernels never touch).  0 = no cap (whatever the registers allow).  Values are rounded
- * down to whole workgroups, never below two workgroups per unit.  Until this is called both are
- * 16, except that a statistics launch over 1 GiB of logits and more runs at 12 (measured on
- * MI355X: 1-4 % faster there, slower on smaller batches). */
+ * down to whole workgroups (two waves for the statistics, four for the residual masses), never
+ * below two workgroups per unit.  Until this is called the statistics run at 12 waves per unit
+ * for bf16 logits and 10 for fp32, the residual masses at 16 (the best settings measured on
+ * MI355X over batches from 160 MB to 5 GB of logits). */
 dssd_status dssd_set_stream_occupancy(dssd_ctx *ctx, int32_t stats_waves_per_cu, int32_t resid_waves_per_cu);
 
 /* ---- kernel timing ---- */

@@ -76,14 +76,12 @@ struct dssd_ctx {
   int32_t cus = 256;                 // compute units of the device
   int64_t lds_per_cu = 160 << 10;    // LDS bytes of one compute unit
   // Streaming kernels run fastest with a moderate number of bytes in flight per compute unit
-  // (measured: read throughput peaks near 16 waves of 8 KiB and falls off by several percent
+  // (measured: read throughput peaks at 10 to 16 waves of 8 KiB and falls off by several percent
   // towards full occupancy).  The caps below are waves per compute unit, enforced by asking for
-  // LDS the kernels never touch; 0 = whatever the registers allow.
-  int32_t stats_waves_per_cu = 16;
+  // LDS the kernels never touch; 0 = whatever the registers allow.  Until the caller sets them the
+  // statistics kernels run at 12 waves for bf16 logits and 10 for fp32, the residual masses at 16.
+  int32_t stats_waves_per_cu = 12;
   int32_t resid_waves_per_cu = 16;
-  // Until the caller sets the caps: a statistics launch over a gigabyte of logits and more runs at
-  // 12 waves per unit (measured 1-4 % faster than 16 there, for either dtype, on shapes from
-  // V = 32 000 to 256 000; 2-5 % slower below 600 MB, where 16 stays).
   bool stats_cap_auto = true;
   int64_t max_rows = 0;
   int32_t max_V = 0;
@@ -309,9 +307,10 @@ struct Timed {
 // Dynamic LDS (bytes per workgroup, never touched by the kernel) that lets at most
 // waves_per_cu / wg_waves workgroups share a compute unit: just more than an (n+1)-th of the
 // unit's LDS.  One workgroup per unit would need more than a launch may ask for: two is the floor.
-// Small grids are left alone: they are bound by latency, not by the memory system.
+// Small grids (under 64 waves per unit in all) are left alone: they are bound by latency, not by
+// the memory system.
 static unsigned occupancy_cap_lds(const dssd_ctx* c, int wg_waves, int waves_per_cu, int64_t grid) {
-  if (waves_per_cu <= 0 || grid < (int64_t)16 * c->cus) return 0;
+  if (waves_per_cu <= 0 || grid * wg_waves < (int64_t)64 * c->cus) return 0;
   const int64_t n = std::max(waves_per_cu / wg_waves, 2);
   const int64_t bytes = (c->lds_per_cu / (n + 1) / 512 + 1) * 512;
   return (unsigned)std::min<int64_t>(bytes, 64 << 10);
@@ -325,9 +324,9 @@ static unsigned accept_threads(const dssd_ctx* c, int32_t B) {
   return (unsigned)(kWave * std::min<int64_t>(4, std::max<int64_t>(1, resident / std::max(B, 1))));
 }
 
-// Waves per compute unit for a statistics launch that reads `bytes` of logits.
-static int32_t stats_waves_for(const dssd_ctx* c, int64_t bytes) {
-  return c->stats_cap_auto && bytes >= ((int64_t)1 << 30) ? 12 : c->stats_waves_per_cu;
+// Waves per compute unit for a statistics launch.
+static int32_t stats_waves_for(const dssd_ctx* c, bool bf16) {
+  return c->stats_cap_auto && !bf16 ? 10 : c->stats_waves_per_cu;
 }
 
 static dssd_status launch_status(const dssd_ctx* c) {
@@ -404,11 +403,11 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
       if (r == 0) {
         const int32_t w = std::min(end, known_rows);
         if ((int64_t)b->B * w * v.C > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;   // 32-bit chunk indices
-        const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
+        const int64_t blocks = ((int64_t)b->B * w * v.C + kStatsWaves - 1) / kStatsWaves;
         with_flags([&](auto BF, auto AL, auto SP) {
-          DSSD_LAUNCH_WG((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, 256,
-                         occupancy_cap_lds(c, 4, stats_waves_for(c, (int64_t)b->B * w * b->V * (bf16 ? 2 : 4)), blocks), s,
-                         v, w, c->open_count, kMaxRounds);
+          DSSD_LAUNCH_WG((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, kStatsWaves * kWave,
+                         occupancy_cap_lds(c, kStatsWaves, stats_waves_for(c, bf16), blocks), s, v, w, c->open_count,
+                         kMaxRounds);
         }, bf16, al, sparse);
       } else {
         // the rows listed by the accept launch before: at most every row that is left
@@ -456,7 +455,7 @@ static dssd_status verify_launches(dssd_ctx* c, const dssd_batch* b, const Batch
     hipLaunchKernelGGL(zero_i32, dim3((unsigned)((v.R_L + 255) / 256)), dim3(256), 0, s, v.support_count, v.R_L);
   {
     Timed t(c, DSSD_K_ROW_STATS, s);
-    const int32_t waves_per_cu = stats_waves_for(c, v.R_L * (int64_t)b->V * (bf16 ? 2 : 4));
+    const int32_t waves_per_cu = stats_waves_for(c, bf16);
     with_flags([&](auto BF, auto AL, auto SP) {
       DSSD_LAUNCH_WG((row_chunk_stats<FLAG(BF), FLAG(AL), FLAG(SP)>), grid, kStatsWaves * kWave,
                      occupancy_cap_lds(c, kStatsWaves, waves_per_cu, grid), s, v);
