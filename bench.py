@@ -29,8 +29,8 @@ MAX_ROUNDS = 8          # early exit: most rounds a step can have
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "c3f9aa90b7c5c01bbe08ebd52d8caafa455ad3749d577504288d2b4ec0af1bbb",
-        "bytes_per_launch": int((2426287.4 * 2.0 + 4776.7 * 1.0) * 1024),
+        "sources_sha256": "eff19c9e12fd28f048f338451996bc3d1bc25f0d6d1daa89f7483898cb4efc7d",
+        "bytes_per_launch": int((2426287.7 * 2.0 + 4776.9 * 1.0) * 1024),
         "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }

@@ -403,11 +403,13 @@ static dssd_status early_exit_launches(dssd_ctx* c, const dssd_batch* b, const B
       if (r == 0) {
         const int32_t w = std::min(end, known_rows);
         if ((int64_t)b->B * w * v.C > 0x7FFFFFFFll) return DSSD_EUNSUPPORTED;   // 32-bit chunk indices
-        const int64_t blocks = ((int64_t)b->B * w * v.C + kStatsWaves - 1) / kStatsWaves;
+        // (this kernel measured best in four-wave workgroups at 16 waves per unit: 0.5-2 % faster
+        // for the whole mode than the two-wave workgroups of row_chunk_stats at any cap)
+        const int64_t blocks = ((int64_t)b->B * w * v.C + 3) / 4;
+        const int32_t waves_per_cu = c->stats_cap_auto ? 16 : c->stats_waves_per_cu;
         with_flags([&](auto BF, auto AL, auto SP) {
-          DSSD_LAUNCH_WG((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, kStatsWaves * kWave,
-                         occupancy_cap_lds(c, kStatsWaves, stats_waves_for(c, bf16), blocks), s, v, w, c->open_count,
-                         kMaxRounds);
+          DSSD_LAUNCH_WG((row_chunk_stats_head<FLAG(BF), FLAG(AL), FLAG(SP)>), blocks, 256,
+                         occupancy_cap_lds(c, 4, waves_per_cu, blocks), s, v, w, c->open_count, kMaxRounds);
         }, bf16, al, sparse);
       } else {
         // the rows listed by the accept launch before: at most every row that is left

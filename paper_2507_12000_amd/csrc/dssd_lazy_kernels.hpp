@@ -40,7 +40,7 @@ struct __attribute__((aligned(16))) RowTask {
 // Round 0: chunk statistics of rows [0, width) of every session, one wave per chunk.
 // zero[0..n_zero) is cleared by the first threads (the list lengths of the rounds that follow).
 template <bool BF16, bool ALIGNED, bool SUPPORT>
-__global__ __launch_bounds__(kStatsWaves * kWave) void row_chunk_stats_head(const BatchView a, int32_t width, ListLengths* zero,
+__global__ __launch_bounds__(256) void row_chunk_stats_head(const BatchView a, int32_t width, ListLengths* zero,
                                                             int32_t n_zero) {
   // wave-uniform 32-bit arithmetic up to the loads, as in row_chunk_stats (the host refuses
   // batches with 2^31 chunk tasks or more)
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kStatsWaves * kWave) void row_chunk_stats_head(cons
   if (blockIdx.x == 0 && threadIdx.x < n_zero) zero[threadIdx.x] = 0;
   const uint32_t C = (uint32_t)a.C;
   const uint32_t per_session = (uint32_t)width * C;
-  const uint32_t task = xcd_contiguous32(blockIdx.x, gridDim.x, a) * kStatsWaves + wave;
+  const uint32_t task = xcd_contiguous32(blockIdx.x, gridDim.x, a) * 4 + wave;
   if (task >= (uint32_t)a.B * per_session) return;
   const int32_t b = (int32_t)(task / per_session);
   const uint32_t rem = task - (uint32_t)b * per_session;
