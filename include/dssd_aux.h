@@ -33,8 +33,8 @@ dssd_status dssd_set_fused_pair_limit(dssd_ctx *ctx, int64_t max_blocks);
  * the kernels never touch).  0 = no cap (whatever the registers allow).  Values are rounded
  * down to whole workgroups (two waves for the statistics, four for the residual masses), never
  * below two workgroups per unit.  Until this is called the statistics run at 12 waves per unit
- * for bf16 logits and 10 for fp32, the residual masses at 16 (the best settings measured on
- * MI355X over batches from 160 MB to 5 GB of logits). */
+ * for bf16 logits and 10 for fp32, the residual masses at 12 and 16 (the best settings measured
+ * on MI355X over batches from 160 MB to 5 GB of logits). */
 dssd_status dssd_set_stream_occupancy(dssd_ctx *ctx, int32_t stats_waves_per_cu, int32_t resid_waves_per_cu);
 
 /* ---- kernel timing ---- */

@@ -79,7 +79,8 @@ struct dssd_ctx {
   // (measured: read throughput peaks at 10 to 16 waves of 8 KiB and falls off by several percent
   // towards full occupancy).  The caps below are waves per compute unit, enforced by asking for
   // LDS the kernels never touch; 0 = whatever the registers allow.  Until the caller sets them the
-  // statistics kernels run at 12 waves for bf16 logits and 10 for fp32, the residual masses at 16.
+  // statistics kernels run at 12 waves for bf16 logits and 10 for fp32, the residual masses at 12
+  // and 16.
   int32_t stats_waves_per_cu = 12;
   int32_t resid_waves_per_cu = 16;
   bool stats_cap_auto = true;
@@ -324,9 +325,12 @@ static unsigned accept_threads(const dssd_ctx* c, int32_t B) {
   return (unsigned)(kWave * std::min<int64_t>(4, std::max<int64_t>(1, resident / std::max(B, 1))));
 }
 
-// Waves per compute unit for a statistics launch.
+// Waves per compute unit for a statistics launch, and for one of the residual masses.
 static int32_t stats_waves_for(const dssd_ctx* c, bool bf16) {
   return c->stats_cap_auto && !bf16 ? 10 : c->stats_waves_per_cu;
+}
+static int32_t resid_waves_for(const dssd_ctx* c, bool bf16) {
+  return c->stats_cap_auto && bf16 ? 12 : c->resid_waves_per_cu;
 }
 
 static dssd_status launch_status(const dssd_ctx* c) {
@@ -511,7 +515,7 @@ extern "C" dssd_status dssd_residual_sample(dssd_ctx* c, const dssd_batch* b, ds
   {
     Timed t(c, DSSD_K_RESID_MASS, s);
     with_flags([&](auto BF, auto AL, auto FP) {
-      DSSD_LAUNCH_WG((resid_mass<FLAG(BF), FLAG(AL), FLAG(FP)>), grid, 256, occupancy_cap_lds(c, 4, c->resid_waves_per_cu, grid), s, v, groups);
+      DSSD_LAUNCH_WG((resid_mass<FLAG(BF), FLAG(AL), FLAG(FP)>), grid, 256, occupancy_cap_lds(c, 4, resid_waves_for(c, bf16), grid), s, v, groups);
     }, bf16, al, fuse);
   }
   if (!fuse) {
