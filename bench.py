@@ -29,8 +29,8 @@ MAX_ROUNDS = 8          # early exit: most rounds a step can have
 # of has changed.
 PMC_TRAFFIC = {
     "cfg4_B1024_ragged_g1-16_V256000_bf16": {
-        "sources_sha256": "78ec91350f158baaa5fc3bfc36be17d1bf2e86e6032fe14321ccaca07d9efeea",
-        "bytes_per_launch": int((2426287.2 * 2.0 + 4776.9 * 1.0) * 1024),
+        "sources_sha256": "356bceb6c3e77400b74ab95efee821a421e29f1cce235e7f0586a8b29a7dd6e9",
+        "bytes_per_launch": int((2426287.5 * 2.0 + 4776.9 * 1.0) * 1024),
         "source": "profiles/step_cfg4_hbm_bytes_pmc.txt (separate rocprofv3 --pmc runs, not this run)",
     },
 }
