@@ -919,6 +919,25 @@ def test_many_sessions():
         big.close()
 
 
+@pytest.mark.parametrize("B", [2500, 3000, 5000])
+def test_accept_workgroups_of_three_two_and_one_waves(B):
+    """Beyond 2 048 sessions the accept kernels run a session's workgroup with fewer than four
+    waves (three at 2 500 sessions, two at 3 000, one at 5 000 on a chip of 256 compute units):
+    every row count from 1 to 10 against the oracle, and the whole-step call agrees bit for bit."""
+    w = synth.Workload(f"accept_waves_B{B}", B=B, V=1000, gamma=0, dtype="bf16", gamma_range=(0, 9),
+                       sigmas=(0.5, 1.5), frac_q_equals_p=0.2, frac_q_uniform=0.1)
+    big = D.Context(DEV, max_rows=w.B * 10, max_V=w.V)
+    try:
+        inputs, gpu, orc, rep = check(big, w, seed=3, step=2, workers=4, gen_seed=9)
+        t, out = D.alloc_out(inputs, DEV)
+        big.step_fused(D.make_batch(inputs, seed=3, step=2), out)
+        torch.cuda.synchronize()
+        for key in gpu:
+            assert np.array_equal(gpu[key], t[key].cpu().numpy(), equal_nan=True), key
+    finally:
+        big.close()
+
+
 def test_two_contexts_on_two_streams_do_not_disturb_each_other(ctx):
     """Two batches in flight, one context and one stream each (the workspaces are per context):
     every step gives what the same call gives alone."""
